@@ -1,0 +1,80 @@
+"""Pure-Python brute force of the SpecKV path for tiny inputs.
+
+TEST INFRASTRUCTURE ONLY: scalar loops and ``math.exp`` / ``math.fsum``, no
+numpy arithmetic, so that a mistake in the vectorised oracle (a dropped term, a
+transposed operand, an off-by-one in the mask or the pooling window) does not
+repeat here.  Same definition and the same readings as ``speckv_oracle``:
+Eq. 1 softmax importance; Alg. 1 row set (window rows, then lookahead rows),
+reduce, pool, select-with-window, gather; GQA groups summed (App. C.2).
+"""
+from __future__ import annotations
+
+import itertools
+import math
+from typing import List, Sequence
+
+
+def raw_scores(q, k, n_window: int, sm_scale: float) -> List[List[float]]:
+    """q[i][h][c], k[j][g][c] nested sequences -> raw[g][j]."""
+    R, Hq, d = len(q), len(q[0]), len(q[0][0])
+    n, Hkv = len(k), len(k[0])
+    G = Hq // Hkv
+    m = n - n_window
+    raw = [[0.0] * n for _ in range(Hkv)]
+    contrib = [[[] for _ in range(n)] for _ in range(Hkv)]
+    for h in range(Hq):
+        g = h // G
+        for i in range(R):
+            last = m + i if i < n_window else n - 1       # last visible key (lookahead rows see all)
+            logits = []
+            for j in range(last + 1):
+                acc = 0.0
+                for c in range(d):
+                    acc += float(q[i][h][c]) * float(k[j][g][c])
+                logits.append(sm_scale * acc)
+            top = max(logits)
+            exps = [math.exp(x - top) for x in logits]
+            denom = math.fsum(exps)
+            for j in range(last + 1):
+                contrib[g][j].append(exps[j] / denom)
+    for g in range(Hkv):
+        for j in range(n):
+            raw[g][j] = math.fsum(contrib[g][j])
+    return raw
+
+
+def max_pool(row: Sequence[float], pool_k: int) -> List[float]:
+    m = len(row)
+    half = pool_k // 2
+    return [max(row[t] for t in range(max(0, j - half), min(m - 1, j + half) + 1)) for j in range(m)]
+
+
+def select_top(pooled: Sequence[float], count: int) -> List[int]:
+    order = sorted(range(len(pooled)), key=lambda j: (-pooled[j], j))
+    return sorted(order[:count])
+
+
+def keep_indices(pooled: Sequence[float], n_in: int, n_window: int, c_max: int) -> List[int]:
+    m = n_in - n_window
+    return select_top(pooled, min(c_max, m)) + list(range(m, n_in))
+
+
+def best_subset_exhaustive(pooled: Sequence[float], count: int) -> List[int]:
+    """Among all `count`-subsets: maximal score sum, then lexicographically smallest."""
+    best_key, best = None, None
+    for comb in itertools.combinations(range(len(pooled)), count):
+        key = (-math.fsum(pooled[j] for j in comb), comb)
+        if best_key is None or key < best_key:
+            best_key, best = key, comb
+    return list(best)
+
+
+def speckv_layer(q, k, v, n_window: int, pool_k: int, c_max: int, sm_scale: float):
+    n, Hkv = len(k), len(k[0])
+    m = n - n_window
+    raw = raw_scores(q, k, n_window, sm_scale)
+    pooled = [max_pool(raw[g][:m], pool_k) for g in range(Hkv)]
+    idx = [keep_indices(pooled[g], n, n_window, c_max) for g in range(Hkv)]
+    k_out = [[list(k[j][g]) for j in idx[g]] for g in range(Hkv)]
+    v_out = [[list(v[j][g]) for j in idx[g]] for g in range(Hkv)]
+    return {"raw": raw, "pooled": pooled, "idx": idx, "k_out": k_out, "v_out": v_out}

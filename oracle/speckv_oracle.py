@@ -1,0 +1,227 @@
+"""CPU float64 oracle for SpecKV importance scoring, selection and cache compaction.
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain definition of what the HIP
+library computes, written from the paper; it is slow on purpose and is never on
+the product path.  Only the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it.  It shares no code with the HIP path.
+
+What it follows (paper notation: n_in prompt tokens, n_window, n_lookahead,
+pool kernel k, budget C_max, m = n_in - n_window):
+
+* importance of a key = attention probability it receives from the observation
+  queries, softmax of scaled dot products (Sec. 3.1, Eq. 1);
+* observation queries = the last n_window prompt rows stacked over the
+  n_lookahead draft rows (Alg. 1, the step that sets m and the CrossAttention
+  step; Sec. 4.1);
+* reduce over queries (Alg. 1 reduce step), local pooling with kernel k
+  (Alg. 1 pooling step; hyper-parameter table: Pool = Max, k = 7);
+* keep the top-scoring non-window keys plus the whole window (Alg. 1 "Select
+  KVs" step; Fig. 2 caption), then cache <- K[i_cache], V[i_cache]
+  (Alg. 1 last step);
+* grouped-query attention: the scores of the query heads that share a KV head
+  are combined into one score per KV head (App. C.2, the GQA note).
+
+Readings taken where the paper is silent or at odds with itself (each is listed
+with its reason in the design notes of this repository):
+
+* reduction over queries and over the heads of a group is a SUM (Eq. 1's mean
+  times a constant), not Alg. 1's max;
+* pooling is MAX pooling (hyper-parameter table), stride 1, same length, the
+  neighbourhood clipped at both ends of the candidate range [0, m);
+* a window row at prompt position p sees keys j <= p (causal); a lookahead row
+  sees every prompt key; the softmax denominator runs over the visible prompt
+  keys only (lookahead keys are not inputs);
+* the budget ``c_max`` counts NON-window keys: C = min(c_max, m) are selected
+  and all n_window window keys are appended, so C + n_window are kept;
+* equal pooled scores at the boundary: the smaller index wins;
+* kept indices are emitted in ascending order (window last).
+
+Parity with the authors' own implementation is UNPINNED: the paper prints no
+numeric example for this path.  The functions below are pinned instead by
+closed forms, invariants, brute force and library compositions in the CPU tests.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- #
+# Scoring (Eq. 1; Alg. 1 CrossAttention + reduce)
+# --------------------------------------------------------------------------- #
+def observation_positions(n_in: int, n_window: int, n_lookahead: int) -> np.ndarray:
+    """Sequence position of each observation row (window rows first).
+
+    Window row i is prompt token m + i; lookahead row t sits after the prompt at
+    n_in + t (Alg. 1: Q from [X_{m:}; Y]).
+    """
+    m = n_in - n_window
+    return np.concatenate([m + np.arange(n_window), n_in + np.arange(n_lookahead)]).astype(np.int64)
+
+
+def attention_probs(q_rows: np.ndarray, k_head: np.ndarray, pos: np.ndarray,
+                    sm_scale: float) -> np.ndarray:
+    """Row softmax of sm_scale * q k^T over the causally visible prompt keys.
+
+    q_rows [R, d], k_head [n, d], pos [R] -> P [R, n]; P[i, j] = 0 for j > pos[i].
+    """
+    q_rows = np.asarray(q_rows, dtype=np.float64)
+    k_head = np.asarray(k_head, dtype=np.float64)
+    n = k_head.shape[0]
+    logits = sm_scale * (q_rows @ k_head.T)                       # [R, n]
+    visible = np.arange(n)[None, :] <= np.asarray(pos)[:, None]   # [R, n]
+    logits = np.where(visible, logits, -np.inf)
+    row_max = logits.max(axis=1, keepdims=True)
+    e = np.exp(logits - row_max)                                  # exp(-inf) = 0
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float) -> np.ndarray:
+    """Importance of every prompt key for every KV head, before pooling.
+
+    q [R, Hq, d] (window rows first), k [n, Hkv, d] -> raw [Hkv, n] with
+    raw[g, j] = sum over the query heads h of group g and over rows i of P_h[i, j].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    R, Hq, _ = q.shape
+    n, Hkv, _ = k.shape
+    if Hq % Hkv:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    G = Hq // Hkv
+    pos = observation_positions(n, n_window, R - n_window)
+    raw = np.zeros((Hkv, n), dtype=np.float64)
+    for g in range(Hkv):
+        for h in range(g * G, (g + 1) * G):
+            raw[g] += attention_probs(q[:, h, :], k[:, g, :], pos, sm_scale).sum(axis=0)
+    return raw
+
+
+# --------------------------------------------------------------------------- #
+# Pooling (Alg. 1 pooling step; table: Max, k = 7)
+# --------------------------------------------------------------------------- #
+def max_pool_1d(x: np.ndarray, pool_k: int) -> np.ndarray:
+    """Same-length max pooling along the last axis, window clipped at the ends."""
+    if pool_k < 1 or pool_k % 2 == 0:
+        raise ValueError("pool_k must be odd and >= 1")
+    x = np.asarray(x, dtype=np.float64)
+    m = x.shape[-1]
+    half = pool_k // 2
+    out = x.copy()
+    for t in range(1, half + 1):
+        if t >= m:
+            break
+        out[..., t:] = np.maximum(out[..., t:], x[..., :-t])      # neighbour j - t
+        out[..., :-t] = np.maximum(out[..., :-t], x[..., t:])     # neighbour j + t
+    return out
+
+
+def pooled_scores(raw: np.ndarray, n_window: int, pool_k: int) -> np.ndarray:
+    """Max-pool the non-window candidates raw[..., :m]; returns [..., m]."""
+    m = raw.shape[-1] - n_window
+    return max_pool_1d(raw[..., :m], pool_k)
+
+
+# --------------------------------------------------------------------------- #
+# Selection (Alg. 1 "Select KVs")
+# --------------------------------------------------------------------------- #
+def select_top(pooled_row: np.ndarray, count: int) -> np.ndarray:
+    """Indices of the `count` largest entries, ties to the smaller index, ascending."""
+    pooled_row = np.asarray(pooled_row)
+    order = np.argsort(-pooled_row, kind="stable")                # stable: ties keep index order
+    return np.sort(order[:count]).astype(np.int64)
+
+
+def keep_indices(pooled_row: np.ndarray, n_in: int, n_window: int, c_max: int) -> np.ndarray:
+    """i_cache for one KV head: top C = min(c_max, m) candidates, then the window."""
+    m = n_in - n_window
+    if pooled_row.shape[-1] != m:
+        raise ValueError("pooled_row must hold the m non-window candidates")
+    C = min(c_max, m)
+    return np.concatenate([select_top(pooled_row, C), np.arange(m, n_in, dtype=np.int64)])
+
+
+# --------------------------------------------------------------------------- #
+# Compaction (Alg. 1 last step)
+# --------------------------------------------------------------------------- #
+def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """x [n, Hkv, d], idx [Hkv, n_keep] -> out [Hkv, n_keep, d] = x[idx[g, r], g, :]."""
+    Hkv = x.shape[1]
+    return np.stack([x[idx[g], g, :] for g in range(Hkv)], axis=0)
+
+
+# --------------------------------------------------------------------------- #
+# Whole path
+# --------------------------------------------------------------------------- #
+def speckv_layer(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window: int,
+                 pool_k: int, c_max: int, sm_scale: float) -> Dict[str, np.ndarray]:
+    """One (sequence, layer): scores -> pooled -> indices -> compacted K/V."""
+    n = k.shape[0]
+    if n < n_window:
+        raise ValueError("n_in must be at least n_window")
+    raw = raw_scores(q, k, n_window, sm_scale)
+    pooled = pooled_scores(raw, n_window, pool_k)
+    idx = np.stack([keep_indices(pooled[g], n, n_window, c_max) for g in range(k.shape[1])])
+    out = {"raw": raw, "pooled": pooled, "idx": idx, "k_out": compact(k, idx)}
+    if v is not None:
+        out["v_out"] = compact(v, idx)
+    return out
+
+
+def speckv_batch(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray],
+                 cu_seqlens: Sequence[int], n_window: int, pool_k: int, c_max: int,
+                 sm_scale: float) -> List[List[Dict[str, np.ndarray]]]:
+    """Every (layer, sequence) of a packed ragged batch.
+
+    q [L, S, R, Hq, d], k/v [L, T, Hkv, d]; returns result[layer][seq] dicts with
+    sequence-local indices.
+    """
+    L, S = q.shape[0], q.shape[1]
+    out = []
+    for layer in range(L):
+        row = []
+        for s in range(S):
+            a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+            row.append(speckv_layer(q[layer, s], k[layer, a:b],
+                                    None if v is None else v[layer, a:b],
+                                    n_window, pool_k, c_max, sm_scale))
+        out.append(row)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Prompt-token selection from draft attention (Sec. 4.2 / Alg. 2, simplified)
+# --------------------------------------------------------------------------- #
+def specpc_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float) -> np.ndarray:
+    """One score per prompt token: probabilities summed over layers, heads, rows.
+
+    q [L, R, Hq, d] (here R = n_window: the last prompt rows only), k [L, n, Hkv, d].
+    """
+    total = np.zeros(k.shape[1], dtype=np.float64)
+    for layer in range(q.shape[0]):
+        total += raw_scores(q[layer], k[layer], n_window, sm_scale).sum(axis=0)
+    return total
+
+
+def expand_neighbors(sel: np.ndarray, n_in: int, n_window: int, n_neighbor: int) -> np.ndarray:
+    """Union of [t - nb, t + nb] for t in sel (clipped to the prompt) and the window."""
+    keep = np.zeros(n_in, dtype=bool)
+    for t in np.asarray(sel, dtype=np.int64):
+        keep[max(0, t - n_neighbor): min(n_in - 1, t + n_neighbor) + 1] = True
+    keep[n_in - n_window:] = True
+    return np.nonzero(keep)[0].astype(np.int64)
+
+
+def specpc_select_tokens(q: np.ndarray, k: np.ndarray, token_ids: np.ndarray, n_window: int,
+                         pool_k: int, top_k: int, n_neighbor: int,
+                         sm_scale: float) -> Dict[str, np.ndarray]:
+    """Cross-layer token selection: sum, max-pool, top-k, +-neighbours, window, gather ids."""
+    n = k.shape[1]
+    m = n - n_window
+    raw = specpc_scores(q, k, n_window, sm_scale)
+    pooled = max_pool_1d(raw[:m], pool_k)
+    sel = select_top(pooled, min(top_k, m))
+    idx = expand_neighbors(sel, n, n_window, n_neighbor)
+    return {"raw": raw, "pooled": pooled, "sel": sel, "idx": idx,
+            "ids": np.asarray(token_ids)[idx], "count": np.int64(idx.shape[0])}
