@@ -1,0 +1,151 @@
+/*
+ * speckv.h - C ABI of the MI355X (gfx950) SpecKV hot path.
+ *
+ * SpecKV (Sec. 4.1, Alg. 1) decides which prompt KV pairs a long-context model keeps
+ * after prefill: the queries of the last n_window prompt tokens and of n_lookahead
+ * draft tokens attend to every prompt key; the attention probabilities (Sec. 3.1,
+ * Eq. 1) are reduced over queries and over the query heads of each GQA group
+ * (App. C.2), smoothed by local pooling with kernel k, and the best-scoring keys plus
+ * the whole window are kept; K and V are then gathered into a compact cache.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers owned by the caller unless a comment says
+ *    HOST.  The library allocates no device memory and keeps no state between calls;
+ *    scratch comes from the caller's workspace (size from *_workspace_bytes).
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and the call returns without synchronising.  Outputs are valid once the
+ *    stream reaches that point.  Inputs are never modified.
+ *  - The return value is the only error channel.  Arguments are validated on the host
+ *    before anything is launched; a failed call has launched nothing.
+ *  - Element strides are in ELEMENTS of `dtype`; the head dimension is contiguous and
+ *    every row (d elements) must start on a 16-byte boundary.
+ *  - Readings of the paper fixed by this library: reduction over queries and group is a
+ *    SUM; pooling is MAX pooling (stride 1, same length, clipped to the non-window
+ *    candidates [0, m), m = n_in - n_window); `c_max` counts NON-window keys, so
+ *    n_keep = min(c_max, m) + n_window rows are kept (pass C_max - n_window to get the
+ *    paper's total budget); ties go to the smaller index; indices come out ascending.
+ *
+ * Layouts (S = n_seqs, L = n_layers, R = n_window + n_lookahead, T = total tokens)
+ * ---------------------------------------------------------------------------------
+ *  q       element (l, s, i, h, c) at l*q_stride_layer + s*q_stride_seq + i*q_stride_row
+ *          + h*q_stride_head + c.  Rows 0..n_window-1 are the queries of prompt
+ *          positions m..n_in-1 (causally masked), rows n_window..R-1 the lookahead
+ *          queries (they see the whole prompt).            (Alg. 1: Q from [X_{m:}; Y])
+ *  k, v    element (l, t, g, c) at l*kv_stride_layer + t*kv_stride_token
+ *          + g*kv_stride_head + c, t = cu_seqlens[s] + j the packed token index.
+ *  scores  (raw / pooled) fp32, per layer T*H_kv values: sequence s starts at
+ *          H_kv*cu_seqlens[s] and holds [H_kv][n_in_s]; layer stride H_kv*T.
+ *          pooled[j] is defined for j < m; entries j >= m are written as 0.
+ *  idx     int32, per layer H_kv*KT values (KT = sum over s of n_keep_s): sequence s
+ *          starts at H_kv*ck[s] (ck = prefix sums of n_keep_s) and holds
+ *          [H_kv][n_keep_s] sequence-local token indices, ascending, window last.
+ *  k_out,  same as idx with d contiguous elements per entry:
+ *  v_out   [L][S packed][H_kv][n_keep_s][d].
+ */
+#ifndef SPECKV_H
+#define SPECKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPECKV_OK = 0,
+  SPECKV_ERR_INVALID_ARG = -1, /* null pointer, bad dimension, misaligned pointer/stride    */
+  SPECKV_ERR_UNSUPPORTED = -2, /* valid request outside what the kernels are built for      */
+  SPECKV_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than required    */
+  SPECKV_ERR_RUNTIME = -4      /* the HIP runtime refused a launch                          */
+} speckv_status;
+
+typedef enum { SPECKV_BF16 = 0, SPECKV_F32 = 1 } speckv_dtype;
+
+#define SPECKV_MAX_SEQS 128     /* sequences per call                                        */
+#define SPECKV_MAX_GROUP_ROWS 4096 /* (n_q_heads / n_kv_heads) * R upper bound               */
+#define SPECKV_MAX_POOL_K 255
+
+/* Problem statement of Alg. 1 (sequence lengths, n_lookahead, C_max, n_window, k) plus
+ * the tensor geometry.  Plain data, read during the call only. */
+typedef struct {
+  int32_t n_seqs;      /* 1..SPECKV_MAX_SEQS                                                 */
+  int32_t n_layers;    /* >= 1                                                               */
+  int32_t n_q_heads;   /* multiple of n_kv_heads; query head h uses KV head h / group        */
+  int32_t n_kv_heads;
+  int32_t head_dim;    /* 64 or 128                                                          */
+  int32_t n_window;    /* >= 0; every sequence needs n_in >= max(1, n_window)                */
+  int32_t n_lookahead; /* >= 0; n_window + n_lookahead >= 1                                  */
+  int32_t pool_k;      /* odd, 1..SPECKV_MAX_POOL_K                                          */
+  int32_t c_max;       /* >= 0: non-window keys kept per KV head (clamped to m)              */
+  float sm_scale;      /* > 0, multiplies q.k (1/sqrt(d), or 1 if folded into q)             */
+  int32_t dtype;       /* speckv_dtype of q, k, v                                            */
+  const int32_t *cu_seqlens; /* HOST, n_seqs+1 non-decreasing token prefix sums starting at 0;
+                                NULL means one sequence of n_in tokens                       */
+  int64_t n_in;        /* used only when cu_seqlens == NULL                                  */
+  int64_t q_stride_layer, q_stride_seq, q_stride_row, q_stride_head;
+  int64_t kv_stride_layer, kv_stride_token, kv_stride_head;
+} speckv_params;
+
+/* Human-readable name of a status code (static storage). */
+const char *speckv_status_string(speckv_status status);
+
+/* Rows of the compacted cache of sequence `seq`: min(c_max, n_in_s - n_window) + n_window
+ * (Alg. 1 "Select KVs": top-k plus the window).  Returns -1 on invalid arguments. */
+int64_t speckv_n_keep(const speckv_params *p, int32_t seq);
+
+/* Sum of speckv_n_keep over all sequences (KT in the layouts above); -1 if invalid. */
+int64_t speckv_total_keep(const speckv_params *p);
+
+/* Bytes of 256-byte-aligned device workspace that speckv_score, speckv_select and
+ * speckv_compress need for these parameters (the maximum over the three).  Returns 0 if
+ * the parameters are invalid. */
+size_t speckv_workspace_bytes(const speckv_params *p);
+
+/* Importance scores (Eq. 1; Alg. 1 CrossAttention, reduce and pooling steps).
+ * For every (layer, sequence, KV head): softmax over the visible prompt keys of
+ * sm_scale*q.k for each observation row of each query head of the group, summed over
+ * rows and heads into raw[j] (all n_in keys), then max-pooled with kernel pool_k over
+ * the candidates j < m into pooled[j].  `raw` may be NULL.  Layout: "scores" above. */
+speckv_status speckv_score(const speckv_params *p, const void *q, const void *k,
+                           float *pooled, float *raw, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Selection (Alg. 1 "Select KVs"; Fig. 2: window always retained).  For every (layer,
+ * sequence, KV head) writes the min(c_max, m) candidates with the largest pooled score
+ * (equal scores: smaller index first), in ascending order, followed by m..n_in-1.
+ * `pooled` must not contain NaN.  Layout: "idx" above. */
+speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Compaction (Alg. 1 last step: cache <- K[i_cache], V[i_cache]).  Bit copy of the rows
+ * named by idx into k_out / v_out.  `v` and `v_out` may both be NULL (keys only).  An
+ * index outside [0, n_in_s) yields a zero row instead of a read.  Needs no workspace. */
+speckv_status speckv_compact(const speckv_params *p, const void *k, const void *v,
+                             const int32_t *idx, void *k_out, void *v_out, void *stream);
+
+/* Fused path: score, select and compact in one call on one stream (Alg. 1 loop body for
+ * every layer, head and sequence).  Pooled scores live in the workspace. */
+speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k,
+                              const void *v, int32_t *idx, void *k_out, void *v_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* Prompt-token selection from draft-model attention (Sec. 4.2 / Alg. 2, in the reduced
+ * form: sum instead of max aggregation, no row weights, no skipped layers).  Needs
+ * n_seqs == 1.  score[j] = attention probability summed over all layers, heads and
+ * observation rows; max-pooled with pool_k over j < m; the top_k best candidates are
+ * each widened to [t - n_neighbor, t + n_neighbor] (clipped to the prompt), united with
+ * the window m..n_in-1 and emitted ascending without duplicates into idx_out
+ * (capacity n_in), with ids_out[r] = token_ids[idx_out[r]] and *count_out (device int32)
+ * the number of entries.  p->c_max is ignored. */
+size_t specpc_workspace_bytes(const speckv_params *p, int32_t top_k);
+speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                   const void *q, const void *k, const int32_t *token_ids,
+                                   int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECKV_H */

@@ -1,0 +1,22 @@
+"""MI355X (gfx950) SpecKV hot path: scoring, selection and KV-cache compaction.
+
+Thin ctypes binding over ``libspeckv.so`` (hand-written HIP, C ABI declared in
+``include/speckv.h``).  PyTorch only supplies device memory and the current
+stream; every step of the path runs in the library's kernels.  There is no CPU
+fallback: calling any function without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    SpecKVError,
+    SpecKVParams,
+    library_path,
+    load_library,
+    n_keep,
+    specpc_select_tokens,
+    specpc_workspace_bytes,
+    speckv_compact,
+    speckv_compress,
+    speckv_score,
+    speckv_select,
+    total_keep,
+    workspace_bytes,
+)

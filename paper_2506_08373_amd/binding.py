@@ -1,0 +1,212 @@
+"""ctypes binding of libspeckv.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks dtype /
+device / contiguity of the innermost dimension, derives the element strides and
+passes raw device pointers plus the current HIP stream through the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libspeckv.so")
+_lib = None
+
+SPECKV_BF16, SPECKV_F32 = 0, 1
+_STATUS = {0: "ok", -1: "invalid argument", -2: "unsupported configuration",
+           -3: "workspace missing, misaligned or too small", -4: "HIP runtime error"}
+
+
+class SpecKVError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__("%s failed: %s (%d)" % (where, _STATUS.get(status, "unknown"), status))
+        self.status = status
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [
+        ("n_seqs", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("n_window", ctypes.c_int32),
+        ("n_lookahead", ctypes.c_int32), ("pool_k", ctypes.c_int32), ("c_max", ctypes.c_int32),
+        ("sm_scale", ctypes.c_float), ("dtype", ctypes.c_int32),
+        ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)), ("n_in", ctypes.c_int64),
+        ("q_stride_layer", ctypes.c_int64), ("q_stride_seq", ctypes.c_int64),
+        ("q_stride_row", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+        ("kv_stride_layer", ctypes.c_int64), ("kv_stride_token", ctypes.c_int64),
+        ("kv_stride_head", ctypes.c_int64),
+    ]
+
+
+EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv_workspace_bytes",
+           "speckv_score", "speckv_select", "speckv_compact", "speckv_compress",
+           "specpc_workspace_bytes", "specpc_select_tokens")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libspeckv.so once.  Raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("libspeckv.so is missing at %s; build it with "
+                           "`python -m paper_2506_08373_amd.build` (needs hipcc)" % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, vp, i32p, f32p = ctypes.POINTER(_CParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    lib.speckv_status_string.restype = ctypes.c_char_p
+    lib.speckv_status_string.argtypes = [ctypes.c_int]
+    lib.speckv_n_keep.restype = ctypes.c_int64
+    lib.speckv_n_keep.argtypes = [P, ctypes.c_int32]
+    lib.speckv_total_keep.restype = ctypes.c_int64
+    lib.speckv_total_keep.argtypes = [P]
+    lib.speckv_workspace_bytes.restype = ctypes.c_size_t
+    lib.speckv_workspace_bytes.argtypes = [P]
+    lib.specpc_workspace_bytes.restype = ctypes.c_size_t
+    lib.specpc_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    lib.speckv_score.restype = ctypes.c_int
+    lib.speckv_score.argtypes = [P, vp, vp, f32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_select.restype = ctypes.c_int
+    lib.speckv_select.argtypes = [P, f32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_compact.restype = ctypes.c_int
+    lib.speckv_compact.argtypes = [P, vp, vp, i32p, vp, vp, vp]
+    lib.speckv_compress.restype = ctypes.c_int
+    lib.speckv_compress.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.specpc_select_tokens.restype = ctypes.c_int
+    lib.specpc_select_tokens.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
+                                         i32p, vp, ctypes.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+class SpecKVParams:
+    """Host-side description of one call (mirrors ``speckv_params``)."""
+
+    def __init__(self, *, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                 seq_lens: Sequence[int], n_window: int, n_lookahead: int, pool_k: int, c_max: int,
+                 sm_scale: float, dtype: torch.dtype,
+                 q_strides: Optional[Tuple[int, int, int, int]] = None,
+                 kv_strides: Optional[Tuple[int, int, int]] = None):
+        self.seq_lens = [int(x) for x in seq_lens]
+        S, R, T = len(self.seq_lens), n_window + n_lookahead, sum(self.seq_lens)
+        if q_strides is None:        # contiguous [L, S, R, Hq, d]
+            q_strides = (S * R * n_q_heads * head_dim, R * n_q_heads * head_dim,
+                         n_q_heads * head_dim, head_dim)
+        if kv_strides is None:       # contiguous [L, T, Hkv, d]
+            kv_strides = (T * n_kv_heads * head_dim, n_kv_heads * head_dim, head_dim)
+        cu = [0]
+        for n in self.seq_lens:
+            cu.append(cu[-1] + n)
+        self._cu = (ctypes.c_int32 * (S + 1))(*cu)
+        self.cu_seqlens = cu
+        self.c = _CParams(
+            n_seqs=S, n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+            n_window=n_window, n_lookahead=n_lookahead, pool_k=pool_k, c_max=c_max, sm_scale=sm_scale,
+            dtype={torch.bfloat16: SPECKV_BF16, torch.float32: SPECKV_F32}[dtype],
+            cu_seqlens=ctypes.cast(self._cu, ctypes.POINTER(ctypes.c_int32)), n_in=0,
+            q_stride_layer=q_strides[0], q_stride_seq=q_strides[1], q_stride_row=q_strides[2],
+            q_stride_head=q_strides[3], kv_stride_layer=kv_strides[0], kv_stride_token=kv_strides[1],
+            kv_stride_head=kv_strides[2])
+        self.torch_dtype = dtype
+        self.n_layers, self.n_kv_heads, self.head_dim = n_layers, n_kv_heads, head_dim
+        self.n_window, self.total_tokens = n_window, T
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+    @classmethod
+    def for_tensors(cls, q: torch.Tensor, k: torch.Tensor, *, seq_lens, n_window, pool_k, c_max,
+                    sm_scale) -> "SpecKVParams":
+        """q [L, S, R, Hq, d], k [L, T, Hkv, d] (any strides with d contiguous)."""
+        if q.dim() != 5 or k.dim() != 4 or q.stride(-1) != 1 or k.stride(-1) != 1:
+            raise ValueError("expected q [L,S,R,Hq,d] and k [L,T,Hkv,d] with contiguous d")
+        L, S, R, Hq, d = q.shape
+        return cls(n_layers=L, n_q_heads=Hq, n_kv_heads=k.shape[2], head_dim=d, seq_lens=seq_lens,
+                   n_window=n_window, n_lookahead=R - n_window, pool_k=pool_k, c_max=c_max,
+                   sm_scale=sm_scale, dtype=q.dtype, q_strides=tuple(q.stride()[:4]),
+                   kv_strides=tuple(k.stride()[:3]))
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libspeckv takes device tensors only")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected %s, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SpecKVError(status, where)
+
+
+def n_keep(p: SpecKVParams, seq: int) -> int:
+    return int(load_library().speckv_n_keep(p.ref(), seq))
+
+
+def total_keep(p: SpecKVParams) -> int:
+    return int(load_library().speckv_total_keep(p.ref()))
+
+
+def workspace_bytes(p: SpecKVParams) -> int:
+    return int(load_library().speckv_workspace_bytes(p.ref()))
+
+
+def specpc_workspace_bytes(p: SpecKVParams, top_k: int) -> int:
+    return int(load_library().specpc_workspace_bytes(p.ref(), top_k))
+
+
+def _ws(ws: Optional[torch.Tensor]) -> Tuple[Optional[int], int]:
+    if ws is None:
+        return None, 0
+    if not ws.is_cuda or not ws.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def speckv_score(p: SpecKVParams, q, k, pooled, raw, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_score(p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+                                       _ptr(pooled, torch.float32), _ptr(raw, torch.float32),
+                                       wp, wb, _stream()), "speckv_score")
+
+
+def speckv_select(p: SpecKVParams, pooled, idx, workspace=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_select(p.ref(), _ptr(pooled, torch.float32), _ptr(idx, torch.int32),
+                                        wp, wb, _stream()), "speckv_select")
+
+
+def speckv_compact(p: SpecKVParams, k, v, idx, k_out, v_out) -> None:
+    _check(load_library().speckv_compact(p.ref(), _ptr(k, p.torch_dtype), _ptr(v, p.torch_dtype),
+                                         _ptr(idx, torch.int32), _ptr(k_out, p.torch_dtype),
+                                         _ptr(v_out, p.torch_dtype), _stream()), "speckv_compact")
+
+
+def speckv_compress(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_compress(p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+                                          _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
+                                          _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
+                                          wp, wb, _stream()), "speckv_compress")
+
+
+def specpc_select_tokens(p: SpecKVParams, top_k: int, n_neighbor: int, q, k, token_ids, idx_out,
+                         ids_out, count_out, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().specpc_select_tokens(
+        p.ref(), top_k, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+        _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
+        _ptr(count_out, torch.int32), wp, wb, _stream()), "specpc_select_tokens")

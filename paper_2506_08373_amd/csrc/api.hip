@@ -1,0 +1,246 @@
+// Host side of libspeckv: argument validation, launch planning, workspace carve-up and the
+// extern "C" entry points declared in speckv.h.  Nothing here touches the device except
+// kernel launches on the caller's stream.
+#include <cmath>
+#include <cstring>
+
+#include "speckv_internal.h"
+
+namespace speckv {
+namespace {
+
+constexpr int64_t kTokenLimit = (int64_t)1 << 30;   // total tokens per call
+constexpr int kTargetWorkgroups = 1024;             // scoring grid: about 4 workgroups per CU
+constexpr int kChunkAlign = 128;                    // chunk = whole LDS key tiles
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Fills the dimension and per-sequence tables.  Returns SPECKV_OK or the reason.
+speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call, int32_t top_k) {
+  if (p == nullptr) return SPECKV_ERR_INVALID_ARG;
+  std::memset(pl, 0, sizeof(*pl));
+  Dims &d = pl->d;
+  if (p->n_seqs < 1 || p->n_layers < 1 || p->n_kv_heads < 1 || p->n_q_heads < 1) return SPECKV_ERR_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return SPECKV_ERR_INVALID_ARG;
+  if (p->n_window < 0 || p->n_lookahead < 0 || p->n_window + (int64_t)p->n_lookahead < 1) return SPECKV_ERR_INVALID_ARG;
+  if (p->pool_k < 1 || p->pool_k % 2 == 0 || p->c_max < 0) return SPECKV_ERR_INVALID_ARG;
+  if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return SPECKV_ERR_INVALID_ARG;
+  if (p->dtype != SPECKV_BF16 && p->dtype != SPECKV_F32) return SPECKV_ERR_INVALID_ARG;
+  if (p->n_seqs > SPECKV_MAX_SEQS) return SPECKV_ERR_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return SPECKV_ERR_UNSUPPORTED;
+  if (p->pool_k > SPECKV_MAX_POOL_K) return SPECKV_ERR_UNSUPPORTED;
+  if (one_row_per_call && p->n_seqs != 1) return SPECKV_ERR_UNSUPPORTED;
+
+  d.L = p->n_layers; d.S = p->n_seqs; d.Hq = p->n_q_heads; d.Hkv = p->n_kv_heads;
+  d.G = d.Hq / d.Hkv; d.D = p->head_dim; d.elt = p->dtype == SPECKV_BF16 ? 2 : 4;
+  d.w = p->n_window; d.a = p->n_lookahead; d.R = d.w + d.a;
+  d.pool_k = p->pool_k; d.c_max = p->c_max; d.sm_scale = p->sm_scale;
+  if ((int64_t)d.G * d.R > SPECKV_MAX_GROUP_ROWS) return SPECKV_ERR_UNSUPPORTED;
+  d.M = d.G * d.R;
+  d.q_sl = p->q_stride_layer; d.q_ss = p->q_stride_seq; d.q_sr = p->q_stride_row; d.q_sh = p->q_stride_head;
+  d.kv_sl = p->kv_stride_layer; d.kv_st = p->kv_stride_token; d.kv_sh = p->kv_stride_head;
+  const int64_t strides[7] = {d.q_sl, d.q_ss, d.q_sr, d.q_sh, d.kv_sl, d.kv_st, d.kv_sh};
+  for (int64_t sv : strides)
+    if (sv < 0 || (sv * d.elt) % 16 != 0) return SPECKV_ERR_INVALID_ARG;
+  if (d.q_sr < d.D || d.q_sh < d.D || d.kv_st < d.D || d.kv_sh < d.D) return SPECKV_ERR_INVALID_ARG;
+
+  SeqTab &t = pl->t;
+  t.n_seqs = d.S;
+  t.cu[0] = 0; t.ck[0] = 0;
+  if (p->cu_seqlens == nullptr) {
+    if (d.S != 1) return SPECKV_ERR_INVALID_ARG;
+    if (p->n_in < 1 || p->n_in > kTokenLimit) return p->n_in < 1 ? SPECKV_ERR_INVALID_ARG : SPECKV_ERR_UNSUPPORTED;
+    t.cu[1] = (int32_t)p->n_in;
+  } else {
+    if (p->cu_seqlens[0] != 0) return SPECKV_ERR_INVALID_ARG;
+    for (int s = 0; s < d.S; ++s) {
+      if (p->cu_seqlens[s + 1] < p->cu_seqlens[s]) return SPECKV_ERR_INVALID_ARG;
+      if ((int64_t)p->cu_seqlens[s + 1] > kTokenLimit) return SPECKV_ERR_UNSUPPORTED;
+      t.cu[s + 1] = p->cu_seqlens[s + 1];
+    }
+  }
+  for (int s = 0; s < d.S; ++s) {
+    const int n_s = t.cu[s + 1] - t.cu[s];
+    if (n_s < 1 || n_s < d.w) return SPECKV_ERR_INVALID_ARG;
+    const int m = n_s - d.w;
+    t.ck[s + 1] = t.ck[s] + (d.c_max < m ? d.c_max : m) + d.w;
+  }
+  d.T = t.cu[d.S];
+  d.KT = t.ck[d.S];
+
+  // scoring geometry
+  ScoreGeom &g = pl->g;
+  const int mb_max = d.D * d.elt <= 256 ? 4 : 2;
+  const int need = (d.M + 127) / 128;
+  g.MB = need >= 3 ? 4 : need;
+  if (g.MB > mb_max) g.MB = mb_max;
+  g.NW = 4;
+  g.RSB = g.NW * g.MB * 32;
+  g.RS = (d.M + g.RSB - 1) / g.RSB;
+  const int64_t units = (int64_t)d.L * d.Hkv * g.RS;
+  if (units > 65535) return SPECKV_ERR_UNSUPPORTED;
+  const int64_t want_chunks = (kTargetWorkgroups + units - 1) / units;
+  int64_t kc = align_up((d.T + want_chunks - 1) / want_chunks, kChunkAlign);
+  if (kc < 4 * kChunkAlign) kc = 4 * kChunkAlign;
+  g.KC = (int32_t)kc;
+  t.cc[0] = 0;
+  for (int s = 0; s < d.S; ++s) {
+    const int n_s = t.cu[s + 1] - t.cu[s];
+    t.cc[s + 1] = t.cc[s] + (n_s + g.KC - 1) / g.KC;
+  }
+  g.n_chunks = t.cc[d.S];
+
+  // workspace carve-up
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = (size_t)align_up((int64_t)(off + bytes), 256); return o; };
+  pl->off_part = take((size_t)units * g.n_chunks * g.RSB * sizeof(float2));
+  pl->off_lse = take((size_t)d.L * d.Hkv * d.S * g.RS * g.RSB * sizeof(float));
+  pl->off_planes = take((size_t)g.RS * d.L * d.Hkv * d.T * sizeof(float));
+  pl->off_pooled = take(one_row_per_call ? (size_t)d.T * sizeof(float) : (size_t)d.L * d.Hkv * d.T * sizeof(float));
+  pl->off_sel = take(one_row_per_call ? (size_t)(top_k > 0 ? top_k : 0) * sizeof(int32_t) : 0);
+  pl->total = off;
+  return SPECKV_OK;
+}
+
+speckv_status check_ws(const Plan &pl, const void *ws, size_t ws_bytes) {
+  if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || ws_bytes < pl.total) return SPECKV_ERR_WORKSPACE;
+  return SPECKV_OK;
+}
+
+speckv_status from_hip(hipError_t e) { return e == hipSuccess ? SPECKV_OK : SPECKV_ERR_RUNTIME; }
+
+}  // namespace
+}  // namespace speckv
+
+using namespace speckv;
+
+extern "C" {
+
+const char *speckv_status_string(speckv_status status) {
+  switch (status) {
+    case SPECKV_OK: return "ok";
+    case SPECKV_ERR_INVALID_ARG: return "invalid argument";
+    case SPECKV_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SPECKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SPECKV_ERR_RUNTIME: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int64_t speckv_n_keep(const speckv_params *p, int32_t seq) {
+  Plan pl;
+  if (build_plan(p, &pl, false, 0) != SPECKV_OK || seq < 0 || seq >= pl.d.S) return -1;
+  return pl.t.ck[seq + 1] - pl.t.ck[seq];
+}
+
+int64_t speckv_total_keep(const speckv_params *p) {
+  Plan pl;
+  if (build_plan(p, &pl, false, 0) != SPECKV_OK) return -1;
+  return pl.d.KT;
+}
+
+size_t speckv_workspace_bytes(const speckv_params *p) {
+  Plan pl;
+  if (build_plan(p, &pl, false, 0) != SPECKV_OK) return 0;
+  return pl.total;
+}
+
+size_t specpc_workspace_bytes(const speckv_params *p, int32_t top_k) {
+  Plan pl;
+  if (top_k < 0 || build_plan(p, &pl, true, top_k) != SPECKV_OK) return 0;
+  return pl.total;
+}
+
+speckv_status speckv_score(const speckv_params *p, const void *q, const void *k, float *pooled,
+                           float *raw, void *workspace, size_t workspace_bytes, void *stream) {
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (q == nullptr || k == nullptr || pooled == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || (reinterpret_cast<uintptr_t>(pooled) & 3u) ||
+      (reinterpret_cast<uintptr_t>(raw) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
+  char *ws = static_cast<char *>(workspace);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
+  hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+  if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return from_hip(launch_reduce_pool(pl, planes, raw, pooled, hs));
+}
+
+speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
+                            void *workspace, size_t workspace_bytes, void *stream) {
+  (void)workspace; (void)workspace_bytes;     // selection keeps its scratch in LDS
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (pooled == nullptr || idx == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(pooled) & 3u) || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  return from_hip(launch_select(pl, pooled, idx, static_cast<hipStream_t>(stream)));
+}
+
+speckv_status speckv_compact(const speckv_params *p, const void *k, const void *v, const int32_t *idx,
+                             void *k_out, void *v_out, void *stream) {
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (k == nullptr || idx == nullptr || k_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((v == nullptr) != (v_out == nullptr)) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+      (reinterpret_cast<uintptr_t>(idx) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  return from_hip(launch_compact(pl, k, v, idx, k_out, v_out, static_cast<hipStream_t>(stream)));
+}
+
+speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k, const void *v,
+                              int32_t *idx, void *k_out, void *v_out, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (q == nullptr || k == nullptr || idx == nullptr || k_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((v == nullptr) != (v_out == nullptr)) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+      (reinterpret_cast<uintptr_t>(idx) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
+  char *ws = static_cast<char *>(workspace);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
+  float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
+  hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+  if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_select(pl, pooled, idx, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return from_hip(launch_compact(pl, k, v, idx, k_out, v_out, hs));
+}
+
+speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                   const void *q, const void *k, const int32_t *token_ids,
+                                   int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                   void *workspace, size_t workspace_bytes, void *stream) {
+  if (top_k < 0 || n_neighbor < 0) return SPECKV_ERR_INVALID_ARG;
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, true, top_k);
+  if (st != SPECKV_OK) return st;
+  if (q == nullptr || k == nullptr || token_ids == nullptr || idx_out == nullptr || ids_out == nullptr ||
+      count_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k)) return SPECKV_ERR_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
+  char *ws = static_cast<char *>(workspace);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const int n_in = (int)pl.d.T, m = n_in - pl.d.w;
+  const int count = top_k < m ? top_k : m;
+  float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
+  float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
+  int32_t *sel = reinterpret_cast<int32_t *>(ws + pl.off_sel);
+  hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+  if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_reduce_pool_all(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_select_row(pooled, m, count, sel, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return from_hip(launch_expand(sel, count, n_in, pl.d.w, n_neighbor, token_ids, idx_out, ids_out,
+                                count_out, hs));
+}
+
+}  // extern "C"

@@ -1,0 +1,345 @@
+// Importance scoring on the gfx950 matrix cores (Sec. 3.1 Eq. 1; Alg. 1 CrossAttention and
+// reduce steps; App. C.2 for the GQA group).
+//
+// For one (layer, sequence, KV head) the logits are S = Qg . K^T with Qg the M = G*R stacked
+// observation rows of the G query heads that share the KV head (row r = head_in_group*R + i)
+// and K the n_in prompt keys of that head.  The importance of key j is the column sum of the
+// row softmax of sm_scale*S.  A column sum needs every row's normaliser first, so S is
+// computed twice and never stored:
+//
+//   pass 1  row statistics: per row the running (max, sum of exp2) over the keys of one chunk;
+//           a small kernel merges the chunks into lse2[row] = log2 sum_j 2^(c*S[row,j]),
+//           c = sm_scale*log2(e).
+//   pass 2  column sums: raw[j] = sum_rows 2^(c*S[row,j] - lse2[row]).
+//
+// Work split: a workgroup owns RSB = NW*MB*32 rows (all of them when M <= RSB) and one chunk of
+// keys.  Each wave keeps the MFMA fragments of its MB 32-row blocks of Q in registers for the
+// whole sweep; K tiles of KT keys stream HBM -> registers -> LDS (double buffered, padded rows
+// so that the 128-bit fragment reads are bank-conflict free) and every wave reads all of them.
+// Pass 1 multiplies with K as the A operand, so a lane holds 16 keys of ONE query row and the
+// row statistics stay in two registers per row block; pass 2 multiplies with Q as the A operand,
+// so a lane holds 16 rows of ONE key and the column sum is an in-lane add, one cross-half add and
+// a cross-wave add through LDS.  No atomics anywhere: results are bit-reproducible.
+//
+// MFMA operand layout used (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32): lane l holds
+// row (A) or column (B) l%32 and the k-slice selected by l/32; the result register i of lane l
+// is element (8*(i/4) + 4*(l/32) + i%4, l%32).  Both operands take their k-slices from the same
+// 16-byte chunks of the head dimension (half l/32 reads chunks [half*NCS, half*NCS+NCS)), so the
+// contraction is over all d channels whatever order the hardware assigns inside a slice.
+#include "speckv_internal.h"
+
+namespace speckv {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
+
+struct ScoreArgs {
+  Dims d;
+  SeqTab t;
+  ScoreGeom g;
+  const char *q;
+  const char *k;
+  float2 *part;     // [unit][chunk][RSB] (max2, sum) per row, unit = (layer, head, row super-block)
+  float *lse;       // [layer][head][seq][RS*RSB]
+  float *planes;    // [RS][layer][Hkv*T]
+};
+
+template <int ELT>
+__device__ inline f32x16 mma_chunk(uint4 a, uint4 b, f32x16 acc);
+
+template <>
+__device__ inline f32x16 mma_chunk<2>(uint4 a, uint4 b, f32x16 acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+template <>
+__device__ inline f32x16 mma_chunk<4>(uint4 a, uint4 b, f32x16 acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  return acc;
+}
+
+template <int ELT, int D>
+struct Tile {
+  static constexpr int ROWB = D * ELT;          // bytes per key / query row
+  static constexpr int C16 = ROWB / 16;         // 16-byte chunks per row
+  static constexpr int NCS = C16 / 2;           // chunk steps (each lane half owns NCS chunks)
+  static constexpr int LSTR = ROWB + 16;        // padded LDS row stride
+  static constexpr int KT = ROWB <= 256 ? 128 : 64;   // keys per LDS tile
+};
+
+template <int ELT, int D, int NW>
+constexpr size_t score_lds_bytes() {
+  using TL = Tile<ELT, D>;
+  return (size_t)2 * TL::KT * TL::LSTR + (size_t)2 * NW * TL::KT * sizeof(float);
+}
+
+template <int ELT, int D, int MB, int NW, int PASS>
+__global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
+  using TL = Tile<ELT, D>;
+  constexpr int C16 = TL::C16, NCS = TL::NCS, LSTR = TL::LSTR, KT = TL::KT;
+  constexpr int NT = NW * 64;
+  constexpr int ITER = KT * C16 / NT;
+  constexpr int RSB = NW * MB * 32;
+  static_assert(KT * C16 % NT == 0 && NT % C16 == 0, "tile load must divide evenly");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char *kbuf = smem;
+  float *csum = reinterpret_cast<float *>(smem + 2 * KT * LSTR);
+
+  const Dims &d = A.d;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int chunk = blockIdx.x;
+  const int unit = blockIdx.y;
+  const int rs = unit % A.g.RS;
+  const int g = (unit / A.g.RS) % d.Hkv;
+  const int layer = unit / (A.g.RS * d.Hkv);
+  int s = 0;
+  while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
+  const int n_s = A.t.cu[s + 1] - A.t.cu[s];
+  const int m = n_s - d.w;
+  const int key_begin = (chunk - A.t.cc[s]) * A.g.KC;
+  const int key_end = min(n_s, key_begin + A.g.KC);
+  const int ntiles = (key_end - key_begin + KT - 1) / KT;
+  const float c2 = d.sm_scale * 1.4426950408889634f;
+
+  // ---- Q fragments of this wave's row blocks, resident for the whole sweep
+  uint4 qf[MB][NCS];
+#pragma unroll
+  for (int rb = 0; rb < MB; ++rb) {
+    const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
+    const bool valid = row < d.M;
+    const int hh = valid ? row / d.R : 0, i = valid ? row % d.R : 0;
+    const char *qp = A.q + ((int64_t)layer * d.q_sl + (int64_t)s * d.q_ss + (int64_t)i * d.q_sr +
+                            (int64_t)(g * d.G + hh) * d.q_sh) * ELT + (half * NCS) * 16;
+#pragma unroll
+    for (int cs = 0; cs < NCS; ++cs)
+      qf[rb][cs] = valid ? *reinterpret_cast<const uint4 *>(qp + cs * 16) : make_uint4(0, 0, 0, 0);
+  }
+
+  // ---- per-pass row state
+  float mrun[MB], lrun[MB];          // pass 1: lane = one query row per row block
+  float nlse[MB][16];                // pass 2: lane = 16 rows per row block
+  if (PASS == 1) {
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) { mrun[rb] = kNegBig; lrun[rb] = 0.f; }
+  } else {
+    const float *lp = A.lse + (((int64_t)layer * d.Hkv + g) * d.S + s) * ((int64_t)A.g.RS * RSB);
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+        nlse[rb][i] = row < d.M ? -lp[row] : -INFINITY;    // padded rows contribute 2^-inf = 0
+      }
+  }
+
+  // ---- K tile staging: thread -> (row, chunk) of the tile
+  const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
+  const int64_t tokb = d.kv_st * ELT;
+  uint4 stage[ITER];
+  // (row, chunk) of the tile element this thread stages in step `it`
+  const int st_row0 = tid / C16, st_c = tid % C16;
+  constexpr int ST_ROWS = NT / C16;                     // tile rows covered per staging step
+  const char *ksrc = kbase + st_c * 16;
+  unsigned char *kdst = kbuf + st_row0 * LSTR + st_c * 16;
+#define SPECKV_LOAD_TILE(tile_)                                                              \
+  {                                                                                          \
+    const int k0_ = key_begin + (tile_) * KT + st_row0;                                      \
+    _Pragma("unroll") for (int it = 0; it < ITER; ++it) {                                    \
+      const int key_ = min(k0_ + it * ST_ROWS, n_s - 1); /* tail rows re-read the last key */ \
+      stage[it] = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)key_ * tokb);             \
+    }                                                                                        \
+  }
+#define SPECKV_STORE_TILE(buf_)                                                              \
+  {                                                                                          \
+    _Pragma("unroll") for (int it = 0; it < ITER; ++it)                                      \
+      *reinterpret_cast<uint4 *>(kdst + (size_t)(buf_) * KT * LSTR + it * ST_ROWS * LSTR) = stage[it]; \
+  }
+  // cross-wave column-sum reduction of one finished tile (pass 2)
+  auto flush_tile = [&](int tile) {
+    if (tid < KT) {
+      const int key = key_begin + tile * KT + tid;
+      if (key < key_end) {
+        const float *cp = csum + (size_t)(tile & 1) * NW * KT + tid;
+        float sum = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) sum += cp[w2 * KT];
+        A.planes[((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s + key] = sum;
+      }
+    }
+  };
+
+  SPECKV_LOAD_TILE(0)
+  SPECKV_STORE_TILE(0)
+  __syncthreads();
+
+  for (int tile = 0; tile < ntiles; ++tile) {
+    const int buf = tile & 1;
+    SPECKV_LOAD_TILE(min(tile + 1, ntiles - 1))      // the last iteration re-reads its own tile
+    if (PASS == 2 && tile > 0) flush_tile(tile - 1);
+    const int tk0 = key_begin + tile * KT;
+    const unsigned char *kb_lds = kbuf + (size_t)buf * KT * LSTR + l32 * LSTR + (half * NCS) * 16;
+#pragma unroll 1
+    for (int kb = 0; kb < KT / 32; ++kb) {
+      if (tk0 + kb * 32 >= key_end) break;               // nothing but padding from here on
+      uint4 bf[NCS];
+#pragma unroll
+      for (int cs = 0; cs < NCS; ++cs)
+        bf[cs] = *reinterpret_cast<const uint4 *>(kb_lds + kb * 32 * LSTR + cs * 16);
+      // keys above m are hidden from some window rows; keys >= n_s do not exist
+      const bool need_mask = tk0 + (kb + 1) * 32 > m;
+      if (PASS == 1) {
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb) {
+          f32x16 acc = {0};
+#pragma unroll
+          for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
+          // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
+          if (need_mask) {
+            const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
+            const int iobs = row % d.R;
+            const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+              if (key > last) acc[i] = -INFINITY;
+            }
+          }
+          float tmax = acc[0];
+#pragma unroll
+          for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+          const float t2 = tmax * c2;
+          if (__any(t2 > mrun[rb])) {
+            const float mnew = fmaxf(mrun[rb], t2);
+            lrun[rb] *= __builtin_amdgcn_exp2f(mrun[rb] - mnew);
+            mrun[rb] = mnew;
+          }
+          const float nm = -mrun[rb];
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nm));
+          lrun[rb] += sum;
+        }
+      } else {
+        float colsum = 0.f;
+        const int key = tk0 + kb * 32 + l32;
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb) {
+          f32x16 acc = {0};
+#pragma unroll
+          for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(qf[rb][cs], bf[cs], acc);
+          // lane: key tk0 + kb*32 + l32; rows (wv*MB+rb)*32 + 8*(i/4) + 4*half + i%4
+          float p[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nlse[rb][i]));
+          if (need_mask) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+              const int iobs = row % d.R;
+              const int last = iobs < d.w ? m + iobs : n_s - 1;
+              if (key > last) p[i] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < 16; ++i) colsum += p[i];
+        }
+        colsum += __shfl_xor(colsum, 32, 64);
+        if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
+      }
+    }
+    if (tile + 1 < ntiles) SPECKV_STORE_TILE(buf ^ 1)
+    __syncthreads();
+  }
+
+  if (PASS == 1) {
+    float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks + chunk) * RSB;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+      const float mo = __shfl_xor(mrun[rb], 32, 64), lo = __shfl_xor(lrun[rb], 32, 64);
+      const float mm = fmaxf(mrun[rb], mo);
+      const float ll = lrun[rb] * __builtin_amdgcn_exp2f(mrun[rb] - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
+      if (half == 0) pp[(wv * MB + rb) * 32 + l32] = make_float2(mm, ll);
+    }
+  } else {
+    flush_tile(ntiles - 1);
+  }
+}
+
+#undef SPECKV_LOAD_TILE
+#undef SPECKV_STORE_TILE
+
+// Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
+__global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs A) {
+  const Dims &d = A.d;
+  const int RSB = A.g.RSB;
+  const int unit = blockIdx.x;            // (layer, head, row super-block)
+  const int s = blockIdx.y;
+  const int rs = unit % A.g.RS;
+  const int lh = unit / A.g.RS;           // layer * Hkv + head
+  const int c0 = A.t.cc[s], c1 = A.t.cc[s + 1];
+  for (int r = threadIdx.x; r < RSB; r += blockDim.x) {
+    const float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks) * RSB + r;
+    float mm = kNegBig;
+    for (int c = c0; c < c1; ++c) mm = fmaxf(mm, pp[(int64_t)c * RSB].x);
+    float ll = 0.f;
+    for (int c = c0; c < c1; ++c) {
+      const float2 v = pp[(int64_t)c * RSB];
+      ll += v.y * exp2f(v.x - mm);
+    }
+    A.lse[((int64_t)lh * d.S + s) * ((int64_t)A.g.RS * RSB) + rs * RSB + r] = mm + log2f(ll);
+  }
+}
+
+template <int ELT, int D, int MB, int NW>
+hipError_t launch_passes(const ScoreArgs &A, hipStream_t st) {
+  const size_t lds = score_lds_bytes<ELT, D, NW>();
+  auto k1 = score_kernel<ELT, D, MB, NW, 1>;
+  auto k2 = score_kernel<ELT, D, MB, NW, 2>;
+  hipError_t e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(A.g.n_chunks, A.d.L * A.d.Hkv * A.g.RS), block(NW * 64);
+  hipLaunchKernelGGL(k1, grid, block, lds, st, A);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS, A.d.S), dim3(256), 0, st, A);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(k2, grid, block, lds, st, A);
+  return hipGetLastError();
+}
+
+template <int ELT, int D>
+hipError_t dispatch_mb(const ScoreArgs &A, hipStream_t st) {
+  switch (A.g.MB) {
+    case 1: return launch_passes<ELT, D, 1, 4>(A, st);
+    case 2: return launch_passes<ELT, D, 2, 4>(A, st);
+    case 4:
+      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 4, 4>(A, st);
+      return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
+                        float *planes, hipStream_t st) {
+  ScoreArgs A;
+  A.d = pl.d; A.t = pl.t; A.g = pl.g;
+  A.q = (const char *)q; A.k = (const char *)k;
+  A.part = part; A.lse = lse; A.planes = planes;
+  if (pl.d.elt == 2) {
+    return pl.d.D == 128 ? dispatch_mb<2, 128>(A, st) : dispatch_mb<2, 64>(A, st);
+  }
+  return pl.d.D == 128 ? dispatch_mb<4, 128>(A, st) : dispatch_mb<4, 64>(A, st);
+}
+
+}  // namespace speckv

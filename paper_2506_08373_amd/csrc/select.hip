@@ -1,0 +1,306 @@
+// Pooling, top-C selection and index expansion.
+//
+//  * reduce_pool: sums the partial score planes the scoring kernels wrote, emits the raw
+//    importance (Eq. 1, summed over queries and the GQA group) and its 1-D max-pool with
+//    kernel k over the non-window candidates (Alg. 1 pooling step; table: Max, k = 7).
+//  * select: the C largest pooled scores per (layer, sequence, KV head), ties to the
+//    smaller index, ascending, then the window m..n_in-1 (Alg. 1 "Select KVs").
+//    MSD radix select on order-preserving 32-bit keys (11 + 11 + 10 bits, LDS
+//    histograms), then an ordered compaction that ranks candidates with wavefront
+//    prefix sums.  One workgroup per row; every step is deterministic.
+//  * expand: widens selected tokens to +-n_neighbor, unites them with the window and
+//    emits the sorted set with the token ids gathered (Sec. 4.2 prompt compression).
+#include "speckv_internal.h"
+
+namespace speckv {
+namespace {
+
+// ----------------------------------------------------------------------------------
+// reduce + pool
+// ----------------------------------------------------------------------------------
+constexpr int kPoolThreads = 256;
+constexpr int kPoolTile = 1024;
+
+// Sums n_planes values per key, writes raw (optional) and pooled for one row tile.
+__device__ inline void reduce_pool_tile(const float *__restrict__ in, int n_planes,
+                                        int64_t plane_stride, float *__restrict__ raw,
+                                        float *__restrict__ pooled, int n_s, int m, int half,
+                                        int j0, float *tile) {
+  const int span = kPoolTile + 2 * half;
+  for (int x = threadIdx.x; x < span; x += kPoolThreads) {
+    const int jj = j0 - half + x;
+    float acc = 0.f;
+    if (jj >= 0 && jj < n_s) {
+      const float *p = in + jj;
+      for (int pl = 0; pl < n_planes; ++pl) acc += p[pl * plane_stride];
+    }
+    tile[x] = acc;
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < kPoolTile; x += kPoolThreads) {
+    const int j = j0 + x;
+    if (j >= n_s) break;
+    const float center = tile[x + half];
+    if (raw != nullptr) raw[j] = center;
+    float best = 0.f;
+    if (j < m) {
+      const int lo = max(0, j - half), hi = min(m - 1, j + half);
+      best = tile[lo - j0 + half];
+      for (int jj = lo + 1; jj <= hi; ++jj) best = fmaxf(best, tile[jj - j0 + half]);
+    }
+    pooled[j] = best;
+  }
+}
+
+__global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
+    Dims d, SeqTab t, int n_planes, int64_t plane_stride, const float *__restrict__ planes,
+    float *__restrict__ raw, float *__restrict__ pooled, int tiles_per_row) {
+  __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
+  const int unit = blockIdx.x / tiles_per_row;
+  const int j0 = (blockIdx.x - unit * tiles_per_row) * kPoolTile;
+  const int g = unit % d.Hkv;
+  const int s = (unit / d.Hkv) % d.S;
+  const int layer = unit / (d.Hkv * d.S);
+  const int n_s = t.cu[s + 1] - t.cu[s];
+  if (j0 >= n_s) return;
+  const int64_t base = (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  reduce_pool_tile(planes + base, n_planes, plane_stride, raw ? raw + base : nullptr,
+                   pooled + base, n_s, n_s - d.w, d.pool_k / 2, j0, tile);
+}
+
+// One output row that sums every plane (all layers, heads, row super-blocks) of a
+// single-sequence call: planes are consecutive rows of n_in floats.
+__global__ __launch_bounds__(kPoolThreads) void reduce_pool_all_kernel(
+    int n_in, int n_window, int pool_k, int n_planes, const float *__restrict__ planes,
+    float *__restrict__ raw, float *__restrict__ pooled) {
+  __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
+  const int j0 = blockIdx.x * kPoolTile;
+  if (j0 >= n_in) return;
+  reduce_pool_tile(planes, n_planes, (int64_t)n_in, raw, pooled, n_in, n_in - n_window,
+                   pool_k / 2, j0, tile);
+}
+
+// ----------------------------------------------------------------------------------
+// radix select
+// ----------------------------------------------------------------------------------
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelPerThread = 4;
+
+// Order-preserving map float -> uint32 (larger float, larger key); -0 counts as +0.
+__device__ inline uint32_t order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+struct SelShared {
+  uint32_t hist[2048];
+  uint32_t wave_tot[2][kSelWaves];
+  uint32_t prefix, remaining;
+};
+
+// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
+// Uses wavefront shuffles for the in-wave scan and LDS for the 16 wave totals.
+__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += up;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w2 = 0; w2 < kSelWaves; ++w2) {
+    const uint32_t x = wave_tot[w2];
+    if (w2 < wave) before += x;
+    all += x;
+  }
+  *total = all;
+  return before + inc - v;
+}
+
+// Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
+// equal values taken from the low-index end.
+__device__ void select_top_row(const float *__restrict__ x, int m, int count,
+                               int32_t *__restrict__ out, SelShared &sh) {
+  const int tid = threadIdx.x;
+  uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
+  const int shifts[3] = {21, 10, 0};
+  const int nbins[3] = {2048, 2048, 1024};
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = shifts[pass], nb = nbins[pass];
+    for (int b = tid; b < 2048; b += kSelThreads) sh.hist[b] = 0;
+    __syncthreads();
+    for (int j = tid; j < m; j += kSelThreads) {
+      const uint32_t key = order_key(x[j]);
+      if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
+    }
+    __syncthreads();
+    // thread t owns the bins nb-1-2t and nb-2-2t: scanning threads in order walks the
+    // bins from the largest digit down.
+    const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+    const uint32_t c0 = b0 >= 0 ? sh.hist[b0] : 0u, c1 = b1 >= 0 ? sh.hist[b1] : 0u;
+    uint32_t total;
+    const uint32_t above = block_exclusive_scan(c0 + c1, sh.wave_tot[0], &total);
+    if (above < remaining && remaining <= above + c0) {
+      sh.prefix = prefix | ((uint32_t)b0 << shift);
+      sh.remaining = remaining - above;
+    } else if (above + c0 < remaining && remaining <= above + c0 + c1) {
+      sh.prefix = prefix | ((uint32_t)b1 << shift);
+      sh.remaining = remaining - above - c0;
+    }
+    __syncthreads();
+    prefix = sh.prefix;
+    remaining = sh.remaining;
+    mask |= (uint32_t)(nb - 1) << shift;
+    __syncthreads();
+  }
+  // prefix is now the key of the count-th largest value; `remaining` of the entries equal
+  // to it are taken, from the low-index end.
+  const uint32_t thr = prefix, need_eq = remaining;
+  uint32_t run_gt = 0, run_eq = 0;
+  int buf = 0;
+  for (int j0 = 0; j0 < m; j0 += kSelThreads * kSelPerThread, buf ^= 1) {
+    const int jb = j0 + tid * kSelPerThread;
+    uint32_t gt_bits = 0, eq_bits = 0, cg = 0, ce = 0;
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) {
+      if (jb + e < m) {
+        const uint32_t key = order_key(x[jb + e]);
+        if (key > thr) { gt_bits |= 1u << e; ++cg; }
+        if (key == thr) { eq_bits |= 1u << e; ++ce; }
+      }
+    }
+    // one scan for both counts: gt in the low 16 bits, eq in the high 16 bits
+    // (a tile holds at most 4096 entries, so neither field can overflow)
+    uint32_t total;
+    const uint32_t before = block_exclusive_scan(cg | (ce << 16), sh.wave_tot[buf], &total);
+    uint32_t gt_before = run_gt + (before & 0xffffu), eq_before = run_eq + (before >> 16);
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) {
+      const bool is_gt = (gt_bits >> e) & 1u, is_eq = (eq_bits >> e) & 1u;
+      if (is_gt || (is_eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = jb + e;
+      gt_before += is_gt;
+      eq_before += is_eq;
+    }
+    run_gt += total & 0xffffu;
+    run_eq += total >> 16;
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(Dims d, SeqTab t,
+                                                             const float *__restrict__ pooled,
+                                                             int32_t *__restrict__ idx) {
+  __shared__ SelShared sh;
+  const int unit = blockIdx.x;
+  const int g = unit % d.Hkv;
+  const int s = (unit / d.Hkv) % d.S;
+  const int layer = unit / (d.Hkv * d.S);
+  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int m = n_s - d.w;
+  const int n_keep = t.ck[s + 1] - t.ck[s];
+  const int count = n_keep - d.w;
+  const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + (int64_t)g * n_keep;
+  for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;   // window, last
+  if (count > 0) select_top_row(row, m, count, out, sh);
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__restrict__ row,
+                                                                 int m, int count,
+                                                                 int32_t *__restrict__ sel) {
+  __shared__ SelShared sh;
+  if (count > 0) select_top_row(row, m, count, sel, sh);
+}
+
+// ----------------------------------------------------------------------------------
+// neighbour expansion (single workgroup)
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void expand_kernel(
+    const int32_t *__restrict__ sel, int count, int n_in, int n_window, int nb,
+    const int32_t *__restrict__ token_ids, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ ids_out, int32_t *__restrict__ count_out) {
+  __shared__ uint32_t wave_tot[2][kSelWaves];
+  const int tid = threadIdx.x;
+  uint32_t written = 0;
+  int buf = 0;
+  // `sel` is ascending, so interval r = [t_r - nb, t_r + nb] only has to be trimmed
+  // against the end of interval r-1 to make the union duplicate-free.
+  for (int r0 = 0; r0 < count; r0 += kSelThreads, buf ^= 1) {
+    const int r = r0 + tid;
+    int start = 0, fresh = 0;
+    if (r < count) {
+      const int tok = sel[r];
+      const int lo = max(0, tok - nb), hi = min(n_in - 1, tok + nb);
+      const int prev_hi = r > 0 ? min(n_in - 1, sel[r - 1] + nb) : -1;
+      start = max(lo, prev_hi + 1);
+      fresh = max(0, hi - start + 1);
+    }
+    uint32_t total;
+    uint32_t pos = written + block_exclusive_scan((uint32_t)fresh, wave_tot[buf], &total);
+    for (int e = 0; e < fresh; ++e) {
+      idx_out[pos + e] = start + e;
+      ids_out[pos + e] = token_ids[start + e];
+    }
+    written += total;
+  }
+  const int m = n_in - n_window;
+  const int last_hi = count > 0 ? min(n_in - 1, sel[count - 1] + nb) : -1;
+  const int wstart = max(m, last_hi + 1);
+  for (int j = wstart + tid; j < n_in; j += kSelThreads) {
+    idx_out[written + (j - wstart)] = j;
+    ids_out[written + (j - wstart)] = token_ids[j];
+  }
+  if (tid == 0) *count_out = (int32_t)written + max(0, n_in - wstart);
+}
+
+}  // namespace
+
+hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
+                              hipStream_t st) {
+  const Dims &d = pl.d;
+  int max_n = 0;
+  for (int s = 0; s < d.S; ++s) max_n = max(max_n, pl.t.cu[s + 1] - pl.t.cu[s]);
+  const int tiles = (max_n + kPoolTile - 1) / kPoolTile;
+  const int64_t blocks = (int64_t)d.L * d.S * d.Hkv * tiles;
+  hipLaunchKernelGGL(reduce_pool_kernel, dim3((unsigned)blocks), dim3(kPoolThreads), 0, st, d, pl.t,
+                     pl.g.RS, (int64_t)d.L * d.Hkv * d.T, planes, raw, pooled, tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *raw, float *pooled,
+                                  hipStream_t st) {
+  const Dims &d = pl.d;
+  const int n_in = (int)d.T;
+  const int tiles = (n_in + kPoolTile - 1) / kPoolTile;
+  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kPoolThreads), 0, st, n_in, d.w,
+                     d.pool_k, pl.g.RS * d.L * d.Hkv, planes, raw, pooled);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st) {
+  const Dims &d = pl.d;
+  const int64_t blocks = (int64_t)d.L * d.S * d.Hkv;
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kSelThreads), 0, st, d, pl.t, pooled, idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_row(const float *pooled_row, int32_t m, int32_t count, int32_t *sel,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(select_row_kernel, dim3(1), dim3(kSelThreads), 0, st, pooled_row, m, count, sel);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand(const int32_t *sel, int32_t count, int32_t n_in, int32_t n_window,
+                         int32_t n_neighbor, const int32_t *token_ids, int32_t *idx_out,
+                         int32_t *ids_out, int32_t *count_out, hipStream_t st) {
+  hipLaunchKernelGGL(expand_kernel, dim3(1), dim3(kSelThreads), 0, st, sel, count, n_in, n_window,
+                     n_neighbor, token_ids, idx_out, ids_out, count_out);
+  return hipGetLastError();
+}
+
+}  // namespace speckv

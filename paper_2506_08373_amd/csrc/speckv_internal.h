@@ -1,0 +1,70 @@
+// Internal plan shared by the host API and the gfx950 kernels of libspeckv.
+// Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "speckv.h"
+
+namespace speckv {
+
+constexpr int kMaxSeqs = SPECKV_MAX_SEQS;
+
+// Per-sequence prefix tables, passed to kernels by value (kernarg segment).
+struct SeqTab {
+  int32_t n_seqs;
+  int32_t cu[kMaxSeqs + 1];   // token prefix sums
+  int32_t ck[kMaxSeqs + 1];   // prefix sums of n_keep_s
+  int32_t cc[kMaxSeqs + 1];   // prefix sums of key chunks (scoring grid)
+};
+
+struct Dims {
+  int32_t L, S, Hq, Hkv, G, D, elt;       // elt = bytes per element (2 bf16, 4 f32)
+  int32_t w, a, R, M;                      // M = G * R rows per KV group
+  int32_t pool_k, c_max;
+  float sm_scale;
+  int64_t q_sl, q_ss, q_sr, q_sh;          // element strides
+  int64_t kv_sl, kv_st, kv_sh;
+  int64_t T, KT;                           // total tokens, total kept rows
+};
+
+// Geometry of the scoring launches (Alg. 1 CrossAttention + reduce).
+struct ScoreGeom {
+  int32_t MB;         // 32-row blocks per wave
+  int32_t NW;         // waves per workgroup
+  int32_t RSB;        // rows per workgroup = NW * MB * 32
+  int32_t RS;         // row super-blocks per KV group = ceil(M / RSB)
+  int32_t KC;         // keys per chunk (multiple of the LDS tile)
+  int32_t n_chunks;   // total chunks over all sequences = cc[S]
+};
+
+struct Plan {
+  Dims d;
+  SeqTab t;
+  ScoreGeom g;
+  // workspace carve-up (byte offsets, 256-aligned)
+  size_t off_part, off_lse, off_planes, off_pooled, off_sel, total;
+};
+
+inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Kernel launchers (each returns the hipError of its launches).
+hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const int32_t *idx,
+                          void *k_out, void *v_out, hipStream_t st);
+hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
+                        float *planes, hipStream_t st);
+// out rows = (layer, seq, head): pooled/raw in the "scores" layout from RS planes.
+hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
+                              hipStream_t st);
+// single output row summing every plane of a one-sequence call (prompt-token selection)
+hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *raw, float *pooled,
+                                  hipStream_t st);
+hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st);
+hipError_t launch_select_row(const float *pooled_row, int32_t m, int32_t count, int32_t *sel,
+                             hipStream_t st);
+hipError_t launch_expand(const int32_t *sel, int32_t count, int32_t n_in, int32_t n_window,
+                         int32_t n_neighbor, const int32_t *token_ids, int32_t *idx_out,
+                         int32_t *ids_out, int32_t *count_out, hipStream_t st);
+
+}  // namespace speckv
