@@ -131,6 +131,18 @@ speckv_status speckv_compress(const speckv_params *p, const void *q, const void 
                               const void *v, int32_t *idx, void *k_out, void *v_out,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* speckv_compress with per-stage timing marks, for benchmarks and profilers.  `events` is a
+ * HOST array of SPECKV_N_STAGE_EVENTS hipEvent_t handles created by the caller; the call
+ * records them on `stream` around its kernels and does not synchronise:
+ *   [0] start  [1] after scoring pass 1 (row statistics)  [2] after the row-statistics merge
+ *   [3] after scoring pass 2 (column sums)  [4] after pooling  [5] after selection
+ *   [6] after compaction.  Same results as speckv_compress (Alg. 1 loop body). */
+#define SPECKV_N_STAGE_EVENTS 7
+speckv_status speckv_compress_events(const speckv_params *p, const void *q, const void *k,
+                                     const void *v, int32_t *idx, void *k_out, void *v_out,
+                                     void *workspace, size_t workspace_bytes, void *stream,
+                                     void **events, int32_t n_events);
+
 /* Prompt-token selection from draft-model attention (Sec. 4.2 / Alg. 2, in the reduced
  * form: sum instead of max aggregation, no row weights, no skipped layers).  Needs
  * n_seqs == 1.  score[j] = attention probability summed over all layers, heads and

@@ -15,6 +15,9 @@ from .binding import (  # noqa: F401
     specpc_workspace_bytes,
     speckv_compact,
     speckv_compress,
+    speckv_compress_events,
+    N_STAGE_EVENTS,
+    STAGE_NAMES,
     speckv_score,
     speckv_select,
     total_keep,

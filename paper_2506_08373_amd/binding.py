@@ -43,6 +43,7 @@ class _CParams(ctypes.Structure):
 
 EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv_workspace_bytes",
            "speckv_score", "speckv_select", "speckv_compact", "speckv_compress",
+           "speckv_compress_events",
            "specpc_workspace_bytes", "specpc_select_tokens")
 
 
@@ -78,6 +79,9 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_compact.argtypes = [P, vp, vp, i32p, vp, vp, vp]
     lib.speckv_compress.restype = ctypes.c_int
     lib.speckv_compress.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.speckv_compress_events.restype = ctypes.c_int
+    lib.speckv_compress_events.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp,
+                                           ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
     lib.specpc_select_tokens.restype = ctypes.c_int
     lib.specpc_select_tokens.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
                                          i32p, vp, ctypes.c_size_t, vp]
@@ -201,6 +205,19 @@ def speckv_compress(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace) -> N
                                           _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
                                           _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
                                           wp, wb, _stream()), "speckv_compress")
+
+
+N_STAGE_EVENTS = 7
+STAGE_NAMES = ("score_pass1", "lse_merge", "score_pass2", "pool", "select", "compact")
+
+
+def speckv_compress_events(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace, events) -> None:
+    """`events`: ctypes array of N_STAGE_EVENTS raw hipEvent_t handles (c_void_p)."""
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_compress_events(
+        p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype), _ptr(v, p.torch_dtype),
+        _ptr(idx, torch.int32), _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype), wp, wb,
+        _stream(), events, N_STAGE_EVENTS), "speckv_compress_events")
 
 
 def specpc_select_tokens(p: SpecKVParams, top_k: int, n_neighbor: int, q, k, token_ids, idx_out,

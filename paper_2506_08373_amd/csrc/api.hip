@@ -192,9 +192,9 @@ speckv_status speckv_compact(const speckv_params *p, const void *k, const void *
   return from_hip(launch_compact(pl, k, v, idx, k_out, v_out, static_cast<hipStream_t>(stream)));
 }
 
-speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k, const void *v,
-                              int32_t *idx, void *k_out, void *v_out, void *workspace,
-                              size_t workspace_bytes, void *stream) {
+static speckv_status compress_impl(const speckv_params *p, const void *q, const void *k, const void *v,
+                                   int32_t *idx, void *k_out, void *v_out, void *workspace,
+                                   size_t workspace_bytes, void *stream, hipEvent_t *ev) {
   Plan pl;
   speckv_status st = build_plan(p, &pl, false, 0);
   if (st != SPECKV_OK) return st;
@@ -208,11 +208,31 @@ speckv_status speckv_compress(const speckv_params *p, const void *q, const void 
   float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
   float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
   hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
-                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev);
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_select(pl, pooled, idx, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
-  return from_hip(launch_compact(pl, k, v, idx, k_out, v_out, hs));
+  if (ev && hipEventRecord(ev[5], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_compact(pl, k, v, idx, k_out, v_out, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if (ev && hipEventRecord(ev[6], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return SPECKV_OK;
+}
+
+speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k, const void *v,
+                              int32_t *idx, void *k_out, void *v_out, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+  return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+speckv_status speckv_compress_events(const speckv_params *p, const void *q, const void *k, const void *v,
+                                     int32_t *idx, void *k_out, void *v_out, void *workspace,
+                                     size_t workspace_bytes, void *stream, void **events, int32_t n_events) {
+  if (events == nullptr || n_events != SPECKV_N_STAGE_EVENTS) return SPECKV_ERR_INVALID_ARG;
+  for (int i = 0; i < n_events; ++i)
+    if (events[i] == nullptr) return SPECKV_ERR_INVALID_ARG;
+  return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream,
+                       reinterpret_cast<hipEvent_t *>(events));
 }
 
 speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,

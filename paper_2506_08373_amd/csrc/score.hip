@@ -298,7 +298,7 @@ __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs A) {
 }
 
 template <int ELT, int D, int MB, int NW>
-hipError_t launch_passes(const ScoreArgs &A, hipStream_t st) {
+hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   const size_t lds = score_lds_bytes<ELT, D, NW>();
   auto k1 = score_kernel<ELT, D, MB, NW, 1>;
   auto k2 = score_kernel<ELT, D, MB, NW, 2>;
@@ -308,21 +308,26 @@ hipError_t launch_passes(const ScoreArgs &A, hipStream_t st) {
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   const dim3 grid(A.g.n_chunks, A.d.L * A.d.Hkv * A.g.RS), block(NW * 64);
+  if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
   hipLaunchKernelGGL(k1, grid, block, lds, st, A);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
   hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS, A.d.S), dim3(256), 0, st, A);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
   hipLaunchKernelGGL(k2, grid, block, lds, st, A);
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
+  return hipSuccess;
 }
 
 template <int ELT, int D>
-hipError_t dispatch_mb(const ScoreArgs &A, hipStream_t st) {
+hipError_t dispatch_mb(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   switch (A.g.MB) {
-    case 1: return launch_passes<ELT, D, 1, 4>(A, st);
-    case 2: return launch_passes<ELT, D, 2, 4>(A, st);
+    case 1: return launch_passes<ELT, D, 1, 4>(A, st, ev);
+    case 2: return launch_passes<ELT, D, 2, 4>(A, st, ev);
     case 4:
-      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 4, 4>(A, st);
+      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 4, 4>(A, st, ev);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
@@ -331,15 +336,15 @@ hipError_t dispatch_mb(const ScoreArgs &A, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
-                        float *planes, hipStream_t st) {
+                        float *planes, hipStream_t st, hipEvent_t *events) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
   A.part = part; A.lse = lse; A.planes = planes;
   if (pl.d.elt == 2) {
-    return pl.d.D == 128 ? dispatch_mb<2, 128>(A, st) : dispatch_mb<2, 64>(A, st);
+    return pl.d.D == 128 ? dispatch_mb<2, 128>(A, st, events) : dispatch_mb<2, 64>(A, st, events);
   }
-  return pl.d.D == 128 ? dispatch_mb<4, 128>(A, st) : dispatch_mb<4, 64>(A, st);
+  return pl.d.D == 128 ? dispatch_mb<4, 128>(A, st, events) : dispatch_mb<4, 64>(A, st, events);
 }
 
 }  // namespace speckv

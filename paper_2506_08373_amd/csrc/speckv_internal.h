@@ -52,8 +52,10 @@ inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + 
 // Kernel launchers (each returns the hipError of its launches).
 hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const int32_t *idx,
                           void *k_out, void *v_out, hipStream_t st);
+// `events`, when not null, holds 4 hipEvent_t recorded before pass 1, before the merge of the
+// row statistics, before pass 2 and after pass 2.
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
-                        float *planes, hipStream_t st);
+                        float *planes, hipStream_t st, hipEvent_t *events = nullptr);
 // out rows = (layer, seq, head): pooled/raw in the "scores" layout from RS planes.
 hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
                               hipStream_t st);
