@@ -70,11 +70,11 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
 
   // scoring geometry
   ScoreGeom &g = pl->g;
-  const int mb_max = d.D * d.elt <= 256 ? 4 : 2;
-  const int need = (d.M + 127) / 128;
-  g.MB = need >= 3 ? 4 : need;
-  if (g.MB > mb_max) g.MB = mb_max;
-  g.NW = 4;
+  // (waves, 32-row blocks per wave): small groups use 4 waves; larger ones 8 waves so that two
+  // waves share each SIMD and the matrix and vector pipes overlap across them.
+  if (d.M <= 128) { g.NW = 4; g.MB = 1; }
+  else if (d.M <= 256 || d.D * d.elt > 256) { g.NW = 8; g.MB = 1; }
+  else { g.NW = 8; g.MB = 2; }
   g.RSB = g.NW * g.MB * 32;
   g.RS = (d.M + g.RSB - 1) / g.RSB;
   const int64_t units = (int64_t)d.L * d.Hkv * g.RS;

@@ -33,6 +33,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
 
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
 
@@ -48,16 +49,16 @@ struct ScoreArgs {
 };
 
 template <int ELT>
-__device__ inline f32x16 mma_chunk(uint4 a, uint4 b, f32x16 acc);
+__device__ inline f32x16 mma_chunk(u32x4 a, u32x4 b, f32x16 acc);
 
 template <>
-__device__ inline f32x16 mma_chunk<2>(uint4 a, uint4 b, f32x16 acc) {
+__device__ inline f32x16 mma_chunk<2>(u32x4 a, u32x4 b, f32x16 acc) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
 
 template <>
-__device__ inline f32x16 mma_chunk<4>(uint4 a, uint4 b, f32x16 acc) {
+__device__ inline f32x16 mma_chunk<4>(u32x4 a, u32x4 b, f32x16 acc) {
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   const float c2 = d.sm_scale * 1.4426950408889634f;
 
   // ---- Q fragments of this wave's row blocks, resident for the whole sweep
-  uint4 qf[MB][NCS];
+  u32x4 qf[MB][NCS];
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
     const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
                             (int64_t)(g * d.G + hh) * d.q_sh) * ELT + (half * NCS) * 16;
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs)
-      qf[rb][cs] = valid ? *reinterpret_cast<const uint4 *>(qp + cs * 16) : make_uint4(0, 0, 0, 0);
+      qf[rb][cs] = valid ? *reinterpret_cast<const u32x4 *>(qp + cs * 16) : (u32x4)(0u);
   }
 
   // ---- per-pass row state
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   // ---- K tile staging: thread -> (row, chunk) of the tile
   const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
   const int64_t tokb = d.kv_st * ELT;
-  uint4 stage[ITER];
+  u32x4 stage[ITER];
   // (row, chunk) of the tile element this thread stages in step `it`
   const int st_row0 = tid / C16, st_c = tid % C16;
   constexpr int ST_ROWS = NT / C16;                     // tile rows covered per staging step
@@ -153,27 +154,28 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
     const int k0_ = key_begin + (tile_) * KT + st_row0;                                      \
     _Pragma("unroll") for (int it = 0; it < ITER; ++it) {                                    \
       const int key_ = min(k0_ + it * ST_ROWS, n_s - 1); /* tail rows re-read the last key */ \
-      stage[it] = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)key_ * tokb);             \
+      stage[it] = *reinterpret_cast<const u32x4 *>(ksrc + (int64_t)key_ * tokb);             \
     }                                                                                        \
   }
 #define SPECKV_STORE_TILE(buf_)                                                              \
   {                                                                                          \
     _Pragma("unroll") for (int it = 0; it < ITER; ++it)                                      \
-      *reinterpret_cast<uint4 *>(kdst + (size_t)(buf_) * KT * LSTR + it * ST_ROWS * LSTR) = stage[it]; \
+      *reinterpret_cast<u32x4 *>(kdst + (size_t)(buf_) * KT * LSTR + it * ST_ROWS * LSTR) = stage[it]; \
   }
   // cross-wave column-sum reduction of one finished tile (pass 2)
-  auto flush_tile = [&](int tile) {
-    if (tid < KT) {
-      const int key = key_begin + tile * KT + tid;
-      if (key < key_end) {
-        const float *cp = csum + (size_t)(tile & 1) * NW * KT + tid;
-        float sum = 0.f;
-#pragma unroll
-        for (int w2 = 0; w2 < NW; ++w2) sum += cp[w2 * KT];
-        A.planes[((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s + key] = sum;
-      }
-    }
-  };
+  float *plane_out = nullptr;
+  if (PASS == 2)
+    plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s;
+#define SPECKV_FLUSH_TILE(tile_)                                                             \
+  if (tid < KT) {                                                                            \
+    const int key_ = key_begin + (tile_) * KT + tid;                                         \
+    if (key_ < key_end) {                                                                    \
+      const float *cp_ = csum + (size_t)((tile_) & 1) * NW * KT + tid;                       \
+      float sum_ = 0.f;                                                                      \
+      _Pragma("unroll") for (int w2 = 0; w2 < NW; ++w2) sum_ += cp_[w2 * KT];                \
+      plane_out[key_] = sum_;                                                                \
+    }                                                                                        \
+  }
 
   SPECKV_LOAD_TILE(0)
   SPECKV_STORE_TILE(0)
@@ -182,16 +184,16 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   for (int tile = 0; tile < ntiles; ++tile) {
     const int buf = tile & 1;
     SPECKV_LOAD_TILE(min(tile + 1, ntiles - 1))      // the last iteration re-reads its own tile
-    if (PASS == 2 && tile > 0) flush_tile(tile - 1);
+    if (PASS == 2 && tile > 0) SPECKV_FLUSH_TILE(tile - 1)
     const int tk0 = key_begin + tile * KT;
     const unsigned char *kb_lds = kbuf + (size_t)buf * KT * LSTR + l32 * LSTR + (half * NCS) * 16;
 #pragma unroll 1
     for (int kb = 0; kb < KT / 32; ++kb) {
       if (tk0 + kb * 32 >= key_end) break;               // nothing but padding from here on
-      uint4 bf[NCS];
+      u32x4 bf[NCS];
 #pragma unroll
       for (int cs = 0; cs < NCS; ++cs)
-        bf[cs] = *reinterpret_cast<const uint4 *>(kb_lds + kb * 32 * LSTR + cs * 16);
+        bf[cs] = *reinterpret_cast<const u32x4 *>(kb_lds + kb * 32 * LSTR + cs * 16);
       // keys above m are hidden from some window rows; keys >= n_s do not exist
       const bool need_mask = tk0 + (kb + 1) * 32 > m;
       if (PASS == 1) {
@@ -268,12 +270,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
       if (half == 0) pp[(wv * MB + rb) * 32 + l32] = make_float2(mm, ll);
     }
   } else {
-    flush_tile(ntiles - 1);
+    SPECKV_FLUSH_TILE(ntiles - 1)
   }
 }
 
 #undef SPECKV_LOAD_TILE
 #undef SPECKV_STORE_TILE
+#undef SPECKV_FLUSH_TILE
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
 __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs A) {
@@ -322,12 +325,13 @@ hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
 }
 
 template <int ELT, int D>
-hipError_t dispatch_mb(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
-  switch (A.g.MB) {
-    case 1: return launch_passes<ELT, D, 1, 4>(A, st, ev);
-    case 2: return launch_passes<ELT, D, 2, 4>(A, st, ev);
-    case 4:
-      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 4, 4>(A, st, ev);
+hipError_t dispatch_geom(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
+  const int code = A.g.NW * 10 + A.g.MB;
+  switch (code) {
+    case 41: return launch_passes<ELT, D, 1, 4>(A, st, ev);
+    case 81: return launch_passes<ELT, D, 1, 8>(A, st, ev);
+    case 82:
+      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 2, 8>(A, st, ev);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
@@ -342,9 +346,9 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
   A.q = (const char *)q; A.k = (const char *)k;
   A.part = part; A.lse = lse; A.planes = planes;
   if (pl.d.elt == 2) {
-    return pl.d.D == 128 ? dispatch_mb<2, 128>(A, st, events) : dispatch_mb<2, 64>(A, st, events);
+    return pl.d.D == 128 ? dispatch_geom<2, 128>(A, st, events) : dispatch_geom<2, 64>(A, st, events);
   }
-  return pl.d.D == 128 ? dispatch_mb<4, 128>(A, st, events) : dispatch_mb<4, 64>(A, st, events);
+  return pl.d.D == 128 ? dispatch_geom<4, 128>(A, st, events) : dispatch_geom<4, 64>(A, st, events);
 }
 
 }  // namespace speckv
