@@ -14,8 +14,10 @@
 //
 // Work split: a workgroup owns RSB = NW*MB*32 rows (all of them when M <= RSB) and one chunk of
 // keys.  Each wave keeps the MFMA fragments of its MB 32-row blocks of Q in registers for the
-// whole sweep; K tiles of KT keys stream HBM -> registers -> LDS (double buffered, padded rows
-// so that the 128-bit fragment reads are bank-conflict free) and every wave reads all of them.
+// whole sweep; K tiles of KT keys stream HBM -> LDS directly (global_load_lds, double buffered,
+// no staging registers).  The LDS tile is unpadded; the 16-byte chunks of a row are stored at
+// slot = chunk ^ swizzle(row) so that the 128-bit fragment reads of 16 consecutive keys hit 16
+// different bank groups.  Every wave reads all K fragments of a tile.
 // Pass 1 multiplies with K as the A operand, so a lane holds 16 keys of ONE query row and the
 // row statistics stay in two registers per row block; pass 2 multiplies with Q as the A operand,
 // so a lane holds 16 rows of ONE key and the column sum is an in-lane add, one cross-half add and
@@ -71,30 +73,34 @@ struct Tile {
   static constexpr int ROWB = D * ELT;          // bytes per key / query row
   static constexpr int C16 = ROWB / 16;         // 16-byte chunks per row
   static constexpr int NCS = C16 / 2;           // chunk steps (each lane half owns NCS chunks)
-  static constexpr int LSTR = ROWB + 16;        // padded LDS row stride
   static constexpr int KT = ROWB <= 256 ? 128 : 64;   // keys per LDS tile
+  static constexpr int TILE_BYTES = KT * ROWB;
+  static constexpr int RPB = ROWB >= 256 ? 1 : 256 / ROWB;   // rows per 256-byte bank sweep
+  static constexpr int SWZ = (C16 < 16 ? C16 : 16) - 1;      // xor mask applied to the chunk index
+  __device__ static inline int swizzle(int row) { return (row / RPB) & SWZ; }
 };
 
 template <int ELT, int D, int NW>
 constexpr size_t score_lds_bytes() {
   using TL = Tile<ELT, D>;
-  return (size_t)2 * TL::KT * TL::LSTR + (size_t)2 * NW * TL::KT * sizeof(float);
+  return (size_t)2 * TL::TILE_BYTES + (size_t)2 * NW * TL::KT * sizeof(float);
 }
 
 template <int ELT, int D, int MB, int NW, int PASS>
 __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   using TL = Tile<ELT, D>;
-  constexpr int C16 = TL::C16, NCS = TL::NCS, LSTR = TL::LSTR, KT = TL::KT;
-  constexpr int NT = NW * 64;
-  constexpr int ITER = KT * C16 / NT;
+  constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
   constexpr int RSB = NW * MB * 32;
-  static_assert(KT * C16 % NT == 0 && NT % C16 == 0, "tile load must divide evenly");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int SEG_PER_WAVE = TILE_BYTES / 1024 / NW;   // 1 KiB (one wave-wide 128-bit load) segments
+  constexpr int RPS = 1024 / ROWB;                        // tile rows per segment
+  static_assert(TILE_BYTES % (1024 * NW) == 0, "tile load must divide evenly over the waves");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char *kbuf = smem;
-  float *csum = reinterpret_cast<float *>(smem + 2 * KT * LSTR);
+  float *csum = reinterpret_cast<float *>(smem + 2 * TILE_BYTES);
 
   const Dims &d = A.d;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int chunk = blockIdx.x;
   const int unit = blockIdx.y;
   const int rs = unit % A.g.RS;
@@ -136,32 +142,37 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-        nlse[rb][i] = row < d.M ? -lp[row] : -INFINITY;    // padded rows contribute 2^-inf = 0
+        const float v = lp[row];                            // the lse buffer covers the padded rows
+        nlse[rb][i] = row < d.M ? -v : -INFINITY;           // padded rows contribute 2^-inf = 0
       }
   }
 
-  // ---- K tile staging: thread -> (row, chunk) of the tile
+  // ---- K tile staging: each wave issues SEG_PER_WAVE wave-wide 128-bit loads that land in LDS
+  // at lds_base + lane*16; the lane picks the global chunk that belongs in its (row, slot).
   const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
   const int64_t tokb = d.kv_st * ELT;
-  u32x4 stage[ITER];
-  // (row, chunk) of the tile element this thread stages in step `it`
-  const int st_row0 = tid / C16, st_c = tid % C16;
-  constexpr int ST_ROWS = NT / C16;                     // tile rows covered per staging step
-  const char *ksrc = kbase + st_c * 16;
-  unsigned char *kdst = kbuf + st_row0 * LSTR + st_c * 16;
-#define SPECKV_LOAD_TILE(tile_)                                                              \
-  {                                                                                          \
-    const int k0_ = key_begin + (tile_) * KT + st_row0;                                      \
-    _Pragma("unroll") for (int it = 0; it < ITER; ++it) {                                    \
-      const int key_ = min(k0_ + it * ST_ROWS, n_s - 1); /* tail rows re-read the last key */ \
-      stage[it] = *reinterpret_cast<const u32x4 *>(ksrc + (int64_t)key_ * tokb);             \
-    }                                                                                        \
+  const int st_row = (lane * 16) / ROWB, st_slot = ((lane * 16) % ROWB) / 16;
+#define SPECKV_LOAD_TILE(tile_, buf_)                                                         \
+  {                                                                                           \
+    const int k0_ = key_begin + (tile_) * KT;                                                 \
+    _Pragma("unroll") for (int it = 0; it < SEG_PER_WAVE; ++it) {                             \
+      const int seg_ = it * NW + wv;                                                          \
+      const int r_ = seg_ * RPS + st_row;                                                     \
+      const int c_ = st_slot ^ TL::swizzle(r_);                                               \
+      const int key_ = min(k0_ + r_, n_s - 1); /* tail rows re-read the last key; masked */   \
+      __builtin_amdgcn_global_load_lds(                                                       \
+          (const __attribute__((address_space(1))) void *)(kbase + (int64_t)key_ * tokb + c_ * 16),   \
+          (__attribute__((address_space(3))) void *)(kbuf + (buf_) * TILE_BYTES + seg_ * 1024), 16, 0, 0); \
+    }                                                                                         \
   }
-#define SPECKV_STORE_TILE(buf_)                                                              \
-  {                                                                                          \
-    _Pragma("unroll") for (int it = 0; it < ITER; ++it)                                      \
-      *reinterpret_cast<u32x4 *>(kdst + (size_t)(buf_) * KT * LSTR + it * ST_ROWS * LSTR) = stage[it]; \
-  }
+  // per-lane LDS offsets of the fragment chunks of key row l32 (same for every 32-key block)
+  uint32_t foff[NCS];
+#pragma unroll
+  for (int cs = 0; cs < NCS; ++cs) foff[cs] = l32 * ROWB + (((half * NCS + cs) ^ TL::swizzle(l32)) * 16);
+#define SPECKV_LOAD_BFRAG(dst_, buf_, kb_)                                                     \
+  _Pragma("unroll") for (int cs = 0; cs < NCS; ++cs)                                          \
+    dst_[cs] = *reinterpret_cast<const u32x4 *>(kbuf + (buf_) * TILE_BYTES + (kb_) * 32 * ROWB + foff[cs]);
+
   // cross-wave column-sum reduction of one finished tile (pass 2)
   float *plane_out = nullptr;
   if (PASS == 2)
@@ -177,86 +188,130 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
     }                                                                                        \
   }
 
-  SPECKV_LOAD_TILE(0)
-  SPECKV_STORE_TILE(0)
+  SPECKV_LOAD_TILE(0, 0)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   for (int tile = 0; tile < ntiles; ++tile) {
     const int buf = tile & 1;
-    SPECKV_LOAD_TILE(min(tile + 1, ntiles - 1))      // the last iteration re-reads its own tile
+    if (tile + 1 < ntiles) SPECKV_LOAD_TILE(tile + 1, buf ^ 1)
     if (PASS == 2 && tile > 0) SPECKV_FLUSH_TILE(tile - 1)
     const int tk0 = key_begin + tile * KT;
-    const unsigned char *kb_lds = kbuf + (size_t)buf * KT * LSTR + l32 * LSTR + (half * NCS) * 16;
-#pragma unroll 1
-    for (int kb = 0; kb < KT / 32; ++kb) {
-      if (tk0 + kb * 32 >= key_end) break;               // nothing but padding from here on
+    if (tk0 + KT <= key_end && tk0 + KT <= m + 1) {
+      // Fast path: every key of the tile exists and is visible to every row (key <= m).
+      // Per 32-key block the MB accumulator chains of this wave are interleaved MFMA by MFMA
+      // (no back-to-back dependent MFMAs); the fragments of the next block are fetched while
+      // the vector pipe turns the scores into probabilities.  The second wave on the SIMD
+      // runs its MFMAs underneath that vector work.
       u32x4 bf[NCS];
+      SPECKV_LOAD_BFRAG(bf, buf, 0)
 #pragma unroll
-      for (int cs = 0; cs < NCS; ++cs)
-        bf[cs] = *reinterpret_cast<const u32x4 *>(kb_lds + kb * 32 * LSTR + cs * 16);
-      // keys above m are hidden from some window rows; keys >= n_s do not exist
-      const bool need_mask = tk0 + (kb + 1) * 32 > m;
-      if (PASS == 1) {
+      for (int kb = 0; kb < KT / 32; ++kb) {
+        f32x16 acc[MB];
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb) {
-          f32x16 acc = {0};
+        for (int rb = 0; rb < MB; ++rb) acc[rb] = (f32x16){0};
 #pragma unroll
-          for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
-          // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
-          if (need_mask) {
-            const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
-            const int iobs = row % d.R;
-            const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
+        for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-              if (key > last) acc[i] = -INFINITY;
-            }
-          }
-          float tmax = acc[0];
+          for (int rb = 0; rb < MB; ++rb)
+            acc[rb] = PASS == 1 ? mma_chunk<ELT>(bf[cs], qf[rb][cs], acc[rb]) : mma_chunk<ELT>(qf[rb][cs], bf[cs], acc[rb]);
+        if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
+        if (PASS == 1) {
 #pragma unroll
-          for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
-          const float t2 = tmax * c2;
-          if (__any(t2 > mrun[rb])) {
-            const float mnew = fmaxf(mrun[rb], t2);
-            lrun[rb] *= __builtin_amdgcn_exp2f(mrun[rb] - mnew);
+          for (int rb = 0; rb < MB; ++rb) {
+            // branch-free online softmax step for the lane's query row
+            float tmax = fmaxf(fmaxf(acc[rb][0], acc[rb][1]), acc[rb][2]);
+#pragma unroll
+            for (int i = 3; i < 15; i += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][i]), acc[rb][i + 1]);
+            tmax = fmaxf(tmax, acc[rb][15]);
+            const float mnew = fmaxf(mrun[rb], tmax * c2);
+            const float scale = __builtin_amdgcn_exp2f(mrun[rb] - mnew);
+            const float nm = -mnew;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nm));
+            lrun[rb] = fmaf(lrun[rb], scale, sum);
             mrun[rb] = mnew;
           }
-          const float nm = -mrun[rb];
-          float sum = 0.f;
+        } else {
+          float colsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nm));
-          lrun[rb] += sum;
+          for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) colsum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nlse[rb][i]));
+          colsum += __shfl_xor(colsum, 32, 64);
+          if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
         }
-      } else {
-        float colsum = 0.f;
-        const int key = tk0 + kb * 32 + l32;
+      }
+    } else {
+      // Slow path (tiles that touch the window or the end of the sequence): masks applied.
+#pragma unroll 1
+      for (int kb = 0; kb < KT / 32; ++kb) {
+        if (tk0 + kb * 32 >= key_end) break;               // nothing but padding from here on
+        u32x4 bf[NCS];
+        SPECKV_LOAD_BFRAG(bf, buf, kb)
+        // keys above m are hidden from some window rows; keys >= n_s do not exist
+        const bool need_mask = tk0 + (kb + 1) * 32 > m;
+        if (PASS == 1) {
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb) {
-          f32x16 acc = {0};
+          for (int rb = 0; rb < MB; ++rb) {
+            f32x16 acc = {0};
 #pragma unroll
-          for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(qf[rb][cs], bf[cs], acc);
-          // lane: key tk0 + kb*32 + l32; rows (wv*MB+rb)*32 + 8*(i/4) + 4*half + i%4
-          float p[16];
-#pragma unroll
-          for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nlse[rb][i]));
-          if (need_mask) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
+            // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
+            if (need_mask) {
+              const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
               const int iobs = row % d.R;
-              const int last = iobs < d.w ? m + iobs : n_s - 1;
-              if (key > last) p[i] = 0.f;
-            }
-          }
+              const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
 #pragma unroll
-          for (int i = 0; i < 16; ++i) colsum += p[i];
+              for (int i = 0; i < 16; ++i) {
+                const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                if (key > last) acc[i] = -INFINITY;
+              }
+            }
+            float tmax = acc[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+            const float mnew = fmaxf(mrun[rb], tmax * c2);
+            const float scale = __builtin_amdgcn_exp2f(mrun[rb] - mnew);
+            const float nm = -mnew;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nm));
+            lrun[rb] = fmaf(lrun[rb], scale, sum);
+            mrun[rb] = mnew;
+          }
+        } else {
+          float colsum = 0.f;
+          const int key = tk0 + kb * 32 + l32;
+#pragma unroll
+          for (int rb = 0; rb < MB; ++rb) {
+            f32x16 acc = {0};
+#pragma unroll
+            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(qf[rb][cs], bf[cs], acc);
+            // lane: key tk0 + kb*32 + l32; rows (wv*MB+rb)*32 + 8*(i/4) + 4*half + i%4
+            float p[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nlse[rb][i]));
+            if (need_mask) {
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                const int iobs = row % d.R;
+                const int last = iobs < d.w ? m + iobs : n_s - 1;
+                if (key > last) p[i] = 0.f;
+              }
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) colsum += p[i];
+          }
+          colsum += __shfl_xor(colsum, 32, 64);
+          if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
         }
-        colsum += __shfl_xor(colsum, 32, 64);
-        if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
       }
     }
-    if (tile + 1 < ntiles) SPECKV_STORE_TILE(buf ^ 1)
+    // the next tile must have landed in LDS, and every wave must be done with this one
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
@@ -275,7 +330,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 }
 
 #undef SPECKV_LOAD_TILE
-#undef SPECKV_STORE_TILE
+#undef SPECKV_LOAD_BFRAG
 #undef SPECKV_FLUSH_TILE
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
