@@ -1,0 +1,168 @@
+"""GPU parity at the full sizes of the benchmark configurations.
+
+The workloads are generated on the GPU (the tensors are too large to draw on the host
+quickly); the oracle gets the same bits by downloading the sampled (layer, sequence)
+slices.  Every layer, sequence and head is checked for the structural properties that
+hold at any size; sampled heads are compared with the float64 oracle element by element.
+The calls use the same launch configuration the benchmark times (one fused
+`speckv_compress` over the whole workload).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import speckv_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-3
+ABS_FLOOR = 1e-6
+
+
+@pytest.fixture(scope="module")
+def S():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2506_08373_amd as lib
+    lib.load_library()
+    return lib
+
+
+def run_workload(S, w, want_scores=True):
+    data = workloads.generate(w, device="cuda")
+    q, k, v = data["q"], data["k"], data["v"]
+    p = S.SpecKVParams.for_tensors(q, k, seq_lens=w.seq_lens, n_window=w.n_window, pool_k=w.pool_k,
+                                   c_max=w.c_max, sm_scale=w.sm_scale)
+    KT, L, H, d = S.total_keep(p), w.n_layers, w.n_kv_heads, w.head_dim
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    k_out = torch.empty((L, H * KT, d), dtype=w.torch_dtype, device="cuda")
+    v_out = torch.empty_like(k_out)
+    ws = torch.empty(S.workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    pooled = None
+    if want_scores:
+        pooled = torch.empty((L, H * w.total_tokens), dtype=torch.float32, device="cuda")
+        S.speckv_score(p, q, k, pooled, None, ws)
+    S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
+    torch.cuda.synchronize()
+    return data, p, idx, k_out, v_out, pooled
+
+
+def keep_layout(w):
+    keeps = [w.n_keep(s) for s in range(w.n_seqs)]
+    return keeps, np.concatenate([[0], np.cumsum(keeps)])
+
+
+def check_structure_everywhere(w, data, idx, k_out, v_out):
+    """Properties that hold at any size, checked on the GPU for every (layer, seq, head)."""
+    keeps, ck = keep_layout(w)
+    cu = w.cu_seqlens
+    H = w.n_kv_heads
+    for s in range(w.n_seqs):
+        n, m, nk = w.seq_lens[s], w.seq_lens[s] - w.n_window, keeps[s]
+        C = nk - w.n_window
+        rows = idx[:, H * ck[s]: H * ck[s + 1]].reshape(w.n_layers, H, nk).long()
+        assert bool((rows[..., 1:] > rows[..., :-1]).all()), "indices not strictly ascending"
+        assert bool((rows[..., 0] >= 0).all()) and bool((rows[..., :C] < m).all())
+        win = torch.arange(m, n, device="cuda")
+        assert bool((rows[..., C:] == win).all()), "window not kept last"
+        planted = data["planted"][:, s]                                    # [L, H, P]
+        hit = (rows[..., None, :C] == planted[..., :, None]).any(-1)       # [L, H, P]
+        assert bool(hit.all()), "a planted heavy hitter was dropped"
+        # compaction is a bit copy of the selected rows
+        view = torch.int16 if w.dtype == "bf16" else torch.int32
+        ksrc = data["k"][:, cu[s]:cu[s + 1]].view(view)                    # [L, n, H, d]
+        vsrc = data["v"][:, cu[s]:cu[s + 1]].view(view)
+        ko = k_out[:, H * ck[s]: H * ck[s + 1]].view(view).reshape(w.n_layers, H, nk, w.head_dim)
+        vo = v_out[:, H * ck[s]: H * ck[s + 1]].view(view).reshape(w.n_layers, H, nk, w.head_dim)
+        for g in range(H):
+            for layer in range(w.n_layers):
+                assert torch.equal(ko[layer, g], ksrc[layer, rows[layer, g], g])
+                assert torch.equal(vo[layer, g], vsrc[layer, rows[layer, g], g])
+
+
+def check_sampled_heads(w, data, idx, pooled, samples):
+    """Element-by-element comparison with the oracle on sampled (layer, seq, head) triples."""
+    keeps, ck = keep_layout(w)
+    cu = w.cu_seqlens
+    H, G = w.n_kv_heads, w.group
+    exact = 0
+    for layer, s, g in samples:
+        n, m = w.seq_lens[s], w.seq_lens[s] - w.n_window
+        qh = workloads.to_float64(data["q"][layer, s, :, g * G:(g + 1) * G])
+        kh = workloads.to_float64(data["k"][layer, cu[s]:cu[s + 1], g:g + 1])
+        raw = orc.raw_scores(qh, kh, w.n_window, w.sm_scale)
+        ref_pooled = orc.pooled_scores(raw, w.n_window, w.pool_k)[0]
+        assert abs(raw.sum() - w.n_rows * G) < 1e-6 * w.n_rows * G        # oracle sanity at this size
+        a = H * cu[s] + g * n
+        got = pooled[layer, a:a + m].double().cpu().numpy()
+        tol = REL_TOL * np.abs(ref_pooled) + ABS_FLOOR * np.abs(ref_pooled).max()
+        bad = np.abs(got - ref_pooled) > tol
+        assert not bad.any(), "pooled scores off at (l%d,s%d,g%d): %d entries" % (layer, s, g, bad.sum())
+        C = keeps[s] - w.n_window
+        b = H * ck[s] + g * keeps[s]
+        sel = idx[layer, b:b + C].cpu().numpy().astype(np.int64)
+        want = orc.select_top(ref_pooled, C)
+        if np.array_equal(sel, want):
+            exact += 1
+            continue
+        tau = np.sort(ref_pooled)[m - C]
+        band = REL_TOL * abs(tau) + ABS_FLOOR * np.abs(ref_pooled).max()
+        assert np.isin(np.nonzero(ref_pooled > tau + band)[0], sel).all()
+        assert not np.isin(np.nonzero(ref_pooled < tau - band)[0], sel).any()
+    return exact
+
+
+def test_llama8b_single_layer_32k_full_oracle(S):
+    w = workloads.llama8b_layer()
+    data, p, idx, k_out, v_out, pooled = run_workload(S, w)
+    check_structure_everywhere(w, data, idx, k_out, v_out)
+    exact = check_sampled_heads(w, data, idx, pooled, [(0, 0, g) for g in range(w.n_kv_heads)])
+    assert exact >= w.n_kv_heads // 2
+
+
+def test_llama8b_full_stack_128k(S):
+    w = workloads.llama8b_full_128k()
+    data, p, idx, k_out, v_out, pooled = run_workload(S, w)
+    check_structure_everywhere(w, data, idx, k_out, v_out)
+    check_sampled_heads(w, data, idx, pooled, [(0, 0, 0), (15, 0, 5), (31, 0, 7)])
+
+
+def test_ragged_batch_full(S):
+    w = workloads.ragged_batch()
+    data, p, idx, k_out, v_out, pooled = run_workload(S, w)
+    check_structure_everywhere(w, data, idx, k_out, v_out)
+    longest = int(np.argmax(w.seq_lens))
+    shortest = int(np.argmin(w.seq_lens))
+    check_sampled_heads(w, data, idx, pooled, [(0, shortest, 0), (27, longest, 3), (13, 4, 2)])
+
+
+def test_specpc_full(S):
+    w = workloads.specpc_draft()
+    top_k, nb = w.c_max, workloads.SPECPC_NEIGHBORS
+    data = workloads.generate(w, device="cuda")
+    ids = workloads.generate_token_ids(w, device="cuda")
+    n = w.seq_lens[0]
+    p = S.SpecKVParams.for_tensors(data["q"], data["k"], seq_lens=w.seq_lens, n_window=w.n_window,
+                                   pool_k=w.pool_k, c_max=w.c_max, sm_scale=w.sm_scale)
+    ws = torch.empty(S.specpc_workspace_bytes(p, top_k), dtype=torch.uint8, device="cuda")
+    idx_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    ids_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    S.specpc_select_tokens(p, top_k, nb, data["q"], data["k"], ids, idx_out, ids_out, count, ws)
+    torch.cuda.synchronize()
+    c = int(count.item())
+    got = idx_out[:c].cpu().numpy().astype(np.int64)
+    assert (np.diff(got) > 0).all() and bool((idx_out[c:] == -1).all())
+    assert torch.equal(ids_out[:c], ids[idx_out[:c].long()])
+    m = n - w.n_window
+    assert got[-w.n_window:].tolist() == list(range(m, n))
+    ref = orc.specpc_select_tokens(workloads.to_float64(data["q"][:, 0]), workloads.to_float64(data["k"]),
+                                   ids.cpu().numpy(), w.n_window, w.pool_k, top_k, nb, w.sm_scale)
+    if np.array_equal(got, ref["idx"]):
+        return
+    tau = np.sort(ref["pooled"])[m - top_k]
+    band = REL_TOL * tau + ABS_FLOOR * ref["pooled"].max()
+    lo = orc.expand_neighbors(np.nonzero(ref["pooled"] > tau + band)[0], n, w.n_window, nb)
+    hi = orc.expand_neighbors(np.nonzero(ref["pooled"] >= tau - band)[0], n, w.n_window, nb)
+    assert np.isin(lo, got).all() and np.isin(got, hi).all()
