@@ -72,6 +72,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 "
+                         "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; sharding over several GPUs is a design note "
@@ -112,6 +115,13 @@ def main() -> int:
                 raise RuntimeError("hipEventCreate failed")
             arr[i] = h
         ev_sets.append(arr)
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
