@@ -180,23 +180,30 @@ def main() -> int:
         except Exception:
             blas_threads = 1
         cores = len(os.sched_getaffinity(0))
-        layer, s = 0, 0
+        s = 0
         cu = w.cu_seqlens
-        qh = workloads.to_float64(q[layer, s])
-        kh = workloads.to_float64(k[layer, cu[s]:cu[s + 1]])
-        vh = workloads.to_float64(v[layer, cu[s]:cu[s + 1]])
-        t0 = time.perf_counter()
-        ref = orc.speckv_layer(qh, kh, vh, w.n_window, w.pool_k, w.c_max, w.sm_scale)
-        cpu_s = time.perf_counter() - t0
         n0 = w.seq_lens[s]
-        cpu_baseline = {"value": round(n0 * H / cpu_s, 1), "unit": "keys/s", "cores": min(cores, blas_threads),
-                        "kind": "oracle", "seconds": round(cpu_s, 2), "host_cores_visible": cores,
-                        "sample": "layer %d, sequence %d of %s (all %d KV heads, n_in=%d): 1/%d of a step"
-                                  % (layer, s, w.name, H, n0, max(1, w.key_units // (n0 * H)))}
         keep0 = w.n_keep(s)
-        got = idx[layer, : H * keep0].reshape(H, keep0).cpu().numpy()
-        parity = {"sample": "layer 0 seq 0", "index_rows_equal_to_oracle":
-                  int(sum(np.array_equal(got[g], ref["idx"][g]) for g in range(H))), "index_rows": H}
+        # bounded sample: about 10 s of oracle time (one 128K layer of the 8B shape takes ~2.5 s)
+        n_sample = max(1, min(L, int(round(4 * (131072 * 8) / (n0 * H)))))
+        layers = sorted(set(int(round(x)) for x in np.linspace(0, L - 1, n_sample)))
+        cpu_s, rows_equal = 0.0, 0
+        for layer in layers:
+            qh = workloads.to_float64(q[layer, s])
+            kh = workloads.to_float64(k[layer, cu[s]:cu[s + 1]])
+            vh = workloads.to_float64(v[layer, cu[s]:cu[s + 1]])
+            t0 = time.perf_counter()
+            ref = orc.speckv_layer(qh, kh, vh, w.n_window, w.pool_k, w.c_max, w.sm_scale)
+            cpu_s += time.perf_counter() - t0
+            got = idx[layer, : H * keep0].reshape(H, keep0).cpu().numpy()
+            rows_equal += int(sum(np.array_equal(got[g], ref["idx"][g]) for g in range(H)))
+        cpu_baseline = {"value": round(len(layers) * n0 * H / cpu_s, 1), "unit": "keys/s",
+                        "cores": min(cores, blas_threads), "kind": "oracle", "seconds": round(cpu_s, 2),
+                        "host_cores_visible": cores,
+                        "sample": "layers %s, sequence %d of %s (all %d KV heads, n_in=%d): %d/%d of a step"
+                                  % (layers, s, w.name, H, n0, len(layers) * n0 * H, w.key_units)}
+        parity = {"sample": "layers %s seq %d" % (layers, s), "index_rows_equal_to_oracle": rows_equal,
+                  "index_rows": H * len(layers)}
 
     out = {
         "metric": "prompt keys scored+compacted/sec (n_in x layers x kv_heads)",

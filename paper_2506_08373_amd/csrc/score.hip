@@ -39,6 +39,14 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit
 
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
 
+
+// x + (x of the lane 32 away), in every lane, without going through LDS (v_permlane32_swap).
+__device__ inline float add_other_half(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 struct ScoreArgs {
   Dims d;
   SeqTab t;
@@ -234,12 +242,24 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
             mrun[rb] = mnew;
           }
         } else {
+          // probabilities in batches of 8: all multiply-adds, then all exp2, then the adds, so
+          // that no instruction waits on the transcendental issued just before it
           float colsum = 0.f;
 #pragma unroll
           for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) colsum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nlse[rb][i]));
-          colsum += __shfl_xor(colsum, 32, 64);
+            for (int h8 = 0; h8 < 16; h8 += 8) {
+              float x[8];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) x[i] = fmaf(acc[rb][h8 + i], c2, nlse[rb][h8 + i]);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
+              __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) colsum += x[i];
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          colsum = add_other_half(colsum);
           if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
         }
       }
@@ -305,7 +325,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) colsum += p[i];
           }
-          colsum += __shfl_xor(colsum, 32, 64);
+          colsum = add_other_half(colsum);
           if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
         }
       }
