@@ -53,9 +53,9 @@ def _hip_runtime() -> ctypes.CDLL:
     return hip
 
 
-def _traffic_from_profile(kernel: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "pmc_traffic_c3.txt")
+def _traffic_from_profile(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % workload)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -163,7 +163,7 @@ def main() -> int:
     dominant = max(("score_pass1", "score_pass2"), key=lambda n: kernels[n]["ms"])
     roofline = {"kernel": dominant, "bound": "mfma", "achieved": kernels[dominant]["achieved"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dominant]["frac"],
-                "traffic": _traffic_from_profile(dominant),
+                "traffic": _traffic_from_profile(dominant, args.workload),
                 "avg_launch_ms": kernels[dominant]["ms"]}
     k_read_gbs = (w.total_tokens * H * d * elt * L) / (kernels[dominant]["ms"] * 1e-3) / 1e9
 

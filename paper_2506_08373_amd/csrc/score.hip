@@ -354,22 +354,41 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #undef SPECKV_FLUSH_TILE
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
-__global__ __launch_bounds__(256) void lse_combine_kernel(ScoreArgs A) {
+// A block covers 64 rows; its 4 waves split the chunks and merge their partial pairs in LDS.
+constexpr int kMergeRows = 64, kMergeSlices = 4;
+
+__device__ inline void merge_pair(float &m, float &l, float m2, float l2) {
+  const float mm = fmaxf(m, m2);
+  l = l * exp2f(m - mm) + l2 * exp2f(m2 - mm);
+  m = mm;
+}
+
+__global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(ScoreArgs A) {
+  __shared__ float2 partial[kMergeSlices][kMergeRows];
   const Dims &d = A.d;
   const int RSB = A.g.RSB;
-  const int unit = blockIdx.x;            // (layer, head, row super-block)
+  const int blocks_per_unit = RSB / kMergeRows;
+  const int unit = blockIdx.x / blocks_per_unit;     // (layer, head, row super-block)
+  const int r = (blockIdx.x % blocks_per_unit) * kMergeRows + (threadIdx.x % kMergeRows);
+  const int slice = threadIdx.x / kMergeRows;
   const int s = blockIdx.y;
   const int rs = unit % A.g.RS;
-  const int lh = unit / A.g.RS;           // layer * Hkv + head
+  const int lh = unit / A.g.RS;                       // layer * Hkv + head
   const int c0 = A.t.cc[s], c1 = A.t.cc[s + 1];
-  for (int r = threadIdx.x; r < RSB; r += blockDim.x) {
-    const float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks) * RSB + r;
-    float mm = kNegBig;
-    for (int c = c0; c < c1; ++c) mm = fmaxf(mm, pp[(int64_t)c * RSB].x);
-    float ll = 0.f;
-    for (int c = c0; c < c1; ++c) {
-      const float2 v = pp[(int64_t)c * RSB];
-      ll += v.y * exp2f(v.x - mm);
+  const float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks) * RSB + r;
+  float mm = kNegBig, ll = 0.f;
+#pragma unroll 4
+  for (int c = c0 + slice; c < c1; c += kMergeSlices) {
+    const float2 v = pp[(int64_t)c * RSB];
+    merge_pair(mm, ll, v.x, v.y);
+  }
+  partial[slice][threadIdx.x % kMergeRows] = make_float2(mm, ll);
+  __syncthreads();
+  if (slice == 0) {
+#pragma unroll
+    for (int k2 = 1; k2 < kMergeSlices; ++k2) {
+      const float2 v = partial[k2][threadIdx.x];
+      merge_pair(mm, ll, v.x, v.y);
     }
     A.lse[((int64_t)lh * d.S + s) * ((int64_t)A.g.RS * RSB) + rs * RSB + r] = mm + log2f(ll);
   }
@@ -390,7 +409,8 @@ hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   hipLaunchKernelGGL(k1, grid, block, lds, st, A);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
-  hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS, A.d.S), dim3(256), 0, st, A);
+  hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS * (A.g.RSB / kMergeRows), A.d.S),
+                     dim3(kMergeRows * kMergeSlices), 0, st, A);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
   hipLaunchKernelGGL(k2, grid, block, lds, st, A);
