@@ -14,13 +14,30 @@ import math
 from typing import List, Sequence
 
 
-def raw_scores(q, k, n_window: int, sm_scale: float) -> List[List[float]]:
+def raw_scores(q, k, n_window: int, sm_scale: float, reduce: str = "sum") -> List[List[float]]:
     """q[i][h][c], k[j][g][c] nested sequences -> raw[g][j]."""
     R, Hq, d = len(q), len(q[0]), len(q[0][0])
     n, Hkv = len(k), len(k[0])
     G = Hq // Hkv
     m = n - n_window
     raw = [[0.0] * n for _ in range(Hkv)]
+    if reduce == "max":
+        # per query head: largest probability any observation row gives the key; heads of a group summed
+        for h in range(Hq):
+            g = h // G
+            best = [0.0] * n
+            for i in range(R):
+                last = m + i if i < n_window else n - 1
+                logits = [sm_scale * sum(float(q[i][h][c]) * float(k[j][g][c]) for c in range(d))
+                          for j in range(last + 1)]
+                top = max(logits)
+                exps = [math.exp(x - top) for x in logits]
+                denom = math.fsum(exps)
+                for j in range(last + 1):
+                    best[j] = max(best[j], exps[j] / denom)
+            for j in range(n):
+                raw[g][j] += best[j]
+        return raw
     contrib = [[[] for _ in range(n)] for _ in range(Hkv)]
     for h in range(Hq):
         g = h // G
@@ -49,6 +66,13 @@ def max_pool(row: Sequence[float], pool_k: int) -> List[float]:
     return [max(row[t] for t in range(max(0, j - half), min(m - 1, j + half) + 1)) for j in range(m)]
 
 
+def avg_pool(row: Sequence[float], pool_k: int) -> List[float]:
+    m = len(row)
+    half = pool_k // 2
+    return [math.fsum(row[t] for t in range(max(0, j - half), min(m - 1, j + half) + 1)) / pool_k
+            for j in range(m)]
+
+
 def select_top(pooled: Sequence[float], count: int) -> List[int]:
     order = sorted(range(len(pooled)), key=lambda j: (-pooled[j], j))
     return sorted(order[:count])
@@ -69,11 +93,13 @@ def best_subset_exhaustive(pooled: Sequence[float], count: int) -> List[int]:
     return list(best)
 
 
-def speckv_layer(q, k, v, n_window: int, pool_k: int, c_max: int, sm_scale: float):
+def speckv_layer(q, k, v, n_window: int, pool_k: int, c_max: int, sm_scale: float,
+                 reduce: str = "sum", pool: str = "max"):
     n, Hkv = len(k), len(k[0])
     m = n - n_window
-    raw = raw_scores(q, k, n_window, sm_scale)
-    pooled = [max_pool(raw[g][:m], pool_k) for g in range(Hkv)]
+    raw = raw_scores(q, k, n_window, sm_scale, reduce)
+    pool_fn = max_pool if pool == "max" else avg_pool
+    pooled = [pool_fn(raw[g][:m], pool_k) for g in range(Hkv)]
     idx = [keep_indices(pooled[g], n, n_window, c_max) for g in range(Hkv)]
     k_out = [[list(k[j][g]) for j in idx[g]] for g in range(Hkv)]
     v_out = [[list(v[j][g]) for j in idx[g]] for g in range(Hkv)]

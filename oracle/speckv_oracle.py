@@ -24,10 +24,16 @@ pool kernel k, budget C_max, m = n_in - n_window):
 Readings taken where the paper is silent or at odds with itself (each is listed
 with its reason in the design notes of this repository):
 
-* reduction over queries and over the heads of a group is a SUM (Eq. 1's mean
-  times a constant), not Alg. 1's max;
-* pooling is MAX pooling (hyper-parameter table), stride 1, same length, the
-  neighbourhood clipped at both ends of the candidate range [0, m);
+* by default the reduction over queries and over the heads of a group is a SUM
+  (Eq. 1's mean times a constant); with reduce="max" (Alg. 1 MaxReduce step;
+  hyper-parameter table "Reduction = Max") it is the maximum over the observation
+  rows of each query head, and the per-head maxima of a GQA group are summed
+  (the group is averaged as in App. C.2, times a constant);
+* by default pooling is MAX pooling (hyper-parameter table), stride 1, same
+  length, the neighbourhood clipped at both ends of the candidate range [0, m);
+  with pool="avg" (Alg. 1 AvgPool1D step) it is the mean over the k positions of
+  the window with zeros outside [0, m) (the usual library convention: padding
+  k//2, padded zeros counted in the divisor);
 * a window row at prompt position p sees keys j <= p (causal); a lookahead row
   sees every prompt key; the softmax denominator runs over the visible prompt
   keys only (lookahead keys are not inputs);
@@ -77,11 +83,14 @@ def attention_probs(q_rows: np.ndarray, k_head: np.ndarray, pos: np.ndarray,
     return e / e.sum(axis=1, keepdims=True)
 
 
-def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float) -> np.ndarray:
+def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float,
+               reduce: str = "sum", row_weights: Optional[np.ndarray] = None,
+               head_reduce: str = "sum") -> np.ndarray:
     """Importance of every prompt key for every KV head, before pooling.
 
-    q [R, Hq, d] (window rows first), k [n, Hkv, d] -> raw [Hkv, n] with
-    raw[g, j] = sum over the query heads h of group g and over rows i of P_h[i, j].
+    q [R, Hq, d] (window rows first), k [n, Hkv, d] -> raw [Hkv, n].  Per query head h the
+    probabilities P_h[i, j] (optionally scaled by row_weights[i]) are reduced over the rows i
+    with `reduce` ("sum" or "max"); the G heads of a group are combined with `head_reduce`.
     """
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -89,12 +98,18 @@ def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float) -> 
     n, Hkv, _ = k.shape
     if Hq % Hkv:
         raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    if reduce not in ("sum", "max") or head_reduce not in ("sum", "max"):
+        raise ValueError("reduce / head_reduce must be 'sum' or 'max'")
     G = Hq // Hkv
     pos = observation_positions(n, n_window, R - n_window)
     raw = np.zeros((Hkv, n), dtype=np.float64)
     for g in range(Hkv):
         for h in range(g * G, (g + 1) * G):
-            raw[g] += attention_probs(q[:, h, :], k[:, g, :], pos, sm_scale).sum(axis=0)
+            P = attention_probs(q[:, h, :], k[:, g, :], pos, sm_scale)
+            if row_weights is not None:
+                P = P * np.asarray(row_weights, dtype=np.float64)[:, None]
+            per_head = P.sum(axis=0) if reduce == "sum" else P.max(axis=0)
+            raw[g] = raw[g] + per_head if head_reduce == "sum" else np.maximum(raw[g], per_head)
     return raw
 
 
@@ -117,10 +132,30 @@ def max_pool_1d(x: np.ndarray, pool_k: int) -> np.ndarray:
     return out
 
 
-def pooled_scores(raw: np.ndarray, n_window: int, pool_k: int) -> np.ndarray:
-    """Max-pool the non-window candidates raw[..., :m]; returns [..., m]."""
+def avg_pool_1d(x: np.ndarray, pool_k: int) -> np.ndarray:
+    """Same-length mean over k positions along the last axis, zeros outside the array."""
+    if pool_k < 1 or pool_k % 2 == 0:
+        raise ValueError("pool_k must be odd and >= 1")
+    x = np.asarray(x, dtype=np.float64)
+    m = x.shape[-1]
+    half = pool_k // 2
+    out = x.copy()
+    for t in range(1, half + 1):
+        if t >= m:
+            break
+        out[..., t:] += x[..., :-t]
+        out[..., :-t] += x[..., t:]
+    return out / pool_k
+
+
+def pooled_scores(raw: np.ndarray, n_window: int, pool_k: int, pool: str = "max") -> np.ndarray:
+    """Pool the non-window candidates raw[..., :m]; returns [..., m]."""
     m = raw.shape[-1] - n_window
-    return max_pool_1d(raw[..., :m], pool_k)
+    if pool == "max":
+        return max_pool_1d(raw[..., :m], pool_k)
+    if pool == "avg":
+        return avg_pool_1d(raw[..., :m], pool_k)
+    raise ValueError("pool must be 'max' or 'avg'")
 
 
 # --------------------------------------------------------------------------- #
@@ -155,13 +190,14 @@ def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
 # Whole path
 # --------------------------------------------------------------------------- #
 def speckv_layer(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window: int,
-                 pool_k: int, c_max: int, sm_scale: float) -> Dict[str, np.ndarray]:
+                 pool_k: int, c_max: int, sm_scale: float, reduce: str = "sum",
+                 pool: str = "max") -> Dict[str, np.ndarray]:
     """One (sequence, layer): scores -> pooled -> indices -> compacted K/V."""
     n = k.shape[0]
     if n < n_window:
         raise ValueError("n_in must be at least n_window")
-    raw = raw_scores(q, k, n_window, sm_scale)
-    pooled = pooled_scores(raw, n_window, pool_k)
+    raw = raw_scores(q, k, n_window, sm_scale, reduce=reduce)
+    pooled = pooled_scores(raw, n_window, pool_k, pool=pool)
     idx = np.stack([keep_indices(pooled[g], n, n_window, c_max) for g in range(k.shape[1])])
     out = {"raw": raw, "pooled": pooled, "idx": idx, "k_out": compact(k, idx)}
     if v is not None:
@@ -171,7 +207,8 @@ def speckv_layer(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window
 
 def speckv_batch(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray],
                  cu_seqlens: Sequence[int], n_window: int, pool_k: int, c_max: int,
-                 sm_scale: float) -> List[List[Dict[str, np.ndarray]]]:
+                 sm_scale: float, reduce: str = "sum",
+                 pool: str = "max") -> List[List[Dict[str, np.ndarray]]]:
     """Every (layer, sequence) of a packed ragged batch.
 
     q [L, S, R, Hq, d], k/v [L, T, Hkv, d]; returns result[layer][seq] dicts with
@@ -185,7 +222,7 @@ def speckv_batch(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray],
             a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
             row.append(speckv_layer(q[layer, s], k[layer, a:b],
                                     None if v is None else v[layer, a:b],
-                                    n_window, pool_k, c_max, sm_scale))
+                                    n_window, pool_k, c_max, sm_scale, reduce=reduce, pool=pool))
         out.append(row)
     return out
 

@@ -366,3 +366,79 @@ def test_stored_c1_expectation_is_current(repo_root):
         fa, fb = dict(x.split("=") for x in a.split()), dict(x.split("=") for x in b.split())
         assert fa["idx_sha"] == fb["idx_sha"] and fa["n_keep"] == fb["n_keep"]
         assert float(fa["pooled_sum"]) == pytest.approx(float(fb["pooled_sum"]), rel=1e-9)
+
+
+# ------------------------------------------------------------------ max reduction / average pooling
+def test_max_reduce_matches_library_and_brute_force():
+    rng = np.random.default_rng(41)
+    w, a, G, Hkv, d, n = 3, 4, 2, 2, 5, 29
+    q, k, _ = _rand_case(rng, w + a, w, G * Hkv, Hkv, d, n, scale=1.3)
+    got = orc.raw_scores(q, k, w, 0.7, reduce="max")
+    m = n - w
+    want = torch.zeros(Hkv, n, dtype=torch.float64)
+    for h in range(G * Hkv):
+        logits = torch.einsum("id,jd->ij", torch.from_numpy(q[:, h]), torch.from_numpy(k[:, h // G])) * 0.7
+        for i in range(w):
+            logits[i, m + i + 1:] = float("-inf")
+        want[h // G] += torch.softmax(logits, dim=1).amax(dim=0)        # library route
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(got, np.array(bf.raw_scores(q.tolist(), k.tolist(), w, 0.7, "max")),
+                               rtol=1e-11, atol=1e-15)
+    total = orc.raw_scores(q, k, w, 0.7, reduce="sum")
+    assert (got <= total + 1e-15).all() and (got * (w + a) >= total - 1e-12).all()   # max <= sum <= R * max
+
+
+def test_max_reduce_closed_form_and_single_row():
+    """Q = 0: a key's best row is the one that sees the fewest keys."""
+    w, a, G, Hkv, d, n = 4, 2, 3, 1, 2, 17
+    m = n - w
+    k = np.random.default_rng(42).standard_normal((n, Hkv, d))
+    raw = orc.raw_scores(np.zeros((w + a, G * Hkv, d)), k, w, 1.0, reduce="max")
+    for j in range(n):
+        first = max(0, j - m)                                   # first window row that sees key j
+        assert raw[0, j] == pytest.approx(G * max(1.0 / n, 1.0 / (m + first + 1)), rel=1e-13)
+    # a single observation row: max and sum coincide
+    q1 = np.random.default_rng(43).standard_normal((1, G, d))
+    np.testing.assert_allclose(orc.raw_scores(q1, k, 0, 1.0, reduce="max"),
+                               orc.raw_scores(q1, k, 0, 1.0, reduce="sum"), rtol=1e-14)
+
+
+def test_row_weights_and_head_max():
+    rng = np.random.default_rng(44)
+    w, a, G, Hkv, d, n = 4, 1, 2, 2, 3, 15
+    q, k, _ = _rand_case(rng, w + a, w, G * Hkv, Hkv, d, n)
+    wts = np.array([0.25, 0.5, 0.75, 1.0, 1.0])
+    got = orc.raw_scores(q, k, w, 1.0, reduce="max", row_weights=wts, head_reduce="max")
+    pos = orc.observation_positions(n, w, a)
+    for g in range(Hkv):
+        stack = np.stack([orc.attention_probs(q[:, h], k[:, g], pos, 1.0) * wts[:, None]
+                          for h in range(g * G, (g + 1) * G)])
+        np.testing.assert_allclose(got[g], stack.max(axis=(0, 1)), rtol=1e-14)
+
+
+@pytest.mark.parametrize("pool_k", [1, 3, 7])
+@pytest.mark.parametrize("m", [1, 4, 50])
+def test_avg_pool_matches_library_and_loop(pool_k, m):
+    x = np.random.default_rng(pool_k + m).random((2, m))
+    got = orc.avg_pool_1d(x, pool_k)
+    lib = F.avg_pool1d(torch.from_numpy(x)[None], pool_k, stride=1, padding=pool_k // 2,
+                       count_include_pad=True)[0].numpy()
+    np.testing.assert_allclose(got, lib, rtol=1e-13, atol=1e-16)
+    for r in range(2):
+        np.testing.assert_allclose(got[r], bf.avg_pool(x[r].tolist(), pool_k), rtol=1e-13)
+    np.testing.assert_allclose(got.sum(), sum(x[:, j].sum() * (min(m - 1, j + pool_k // 2) - max(0, j - pool_k // 2) + 1)
+                                              for j in range(m)) / pool_k, rtol=1e-12)
+
+
+def test_paper_setting_end_to_end_vs_brute_force():
+    """Max reduction + average pooling (the Alg. 1 listing) through the whole path."""
+    for seed in range(4):
+        rng = np.random.default_rng(200 + seed)
+        w, a, G, Hkv, d = int(rng.integers(0, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 3)), 2, 3
+        n = int(rng.integers(w + 2, 16))
+        q, k, v = _rand_case(rng, w + a, w, G * Hkv, Hkv, d, n, scale=1.5)
+        for reduce, pool in (("max", "avg"), ("max", "max"), ("sum", "avg")):
+            got = orc.speckv_layer(q, k, v, w, 5, 4, 0.9, reduce=reduce, pool=pool)
+            want = bf.speckv_layer(q.tolist(), k.tolist(), v.tolist(), w, 5, 4, 0.9, reduce, pool)
+            np.testing.assert_allclose(got["pooled"], np.array(want["pooled"]).reshape(Hkv, n - w), rtol=1e-11, atol=1e-15)
+            assert got["idx"].tolist() == want["idx"]
