@@ -20,9 +20,10 @@
  *    before anything is launched; a failed call has launched nothing.
  *  - Element strides are in ELEMENTS of `dtype`; the head dimension is contiguous and
  *    every row (d elements) must start on a 16-byte boundary.
- *  - Readings of the paper fixed by this library: reduction over queries and group is a
- *    SUM; pooling is MAX pooling (stride 1, same length, clipped to the non-window
- *    candidates [0, m), m = n_in - n_window); `c_max` counts NON-window keys, so
+ *  - Readings of the paper fixed by this library: by default the reduction over queries and
+ *    group is a SUM and pooling is MAX pooling (stride 1, same length, clipped to the
+ *    non-window candidates [0, m), m = n_in - n_window); reduce_op / pool_op select the
+ *    listing's max reduction and average pooling; `c_max` counts NON-window keys, so
  *    n_keep = min(c_max, m) + n_window rows are kept (pass C_max - n_window to get the
  *    paper's total budget); ties go to the smaller index; indices come out ascending.
  *
@@ -63,6 +64,17 @@ typedef enum {
 
 typedef enum { SPECKV_BF16 = 0, SPECKV_F32 = 1 } speckv_dtype;
 
+/* Reduction over the observation rows of one query head (Alg. 1 reduce step).  SUM is Eq. 1's
+ * mean times a constant; MAX is the listing's MaxReduce (hyper-parameter table "Reduction =
+ * Max").  Either way the per-head results of a GQA group are added (App. C.2 averages them). */
+typedef enum { SPECKV_REDUCE_SUM = 0, SPECKV_REDUCE_MAX = 1 } speckv_reduce_op;
+
+/* Local pooling with kernel pool_k (Alg. 1 pooling step).  MAX: neighbourhood clipped to the
+ * candidates [0, m) (hyper-parameter table).  AVG: mean over the pool_k positions with zeros
+ * outside [0, m), i.e. the divisor is always pool_k (the listing's AvgPool1D with the usual
+ * library padding convention). */
+typedef enum { SPECKV_POOL_MAX = 0, SPECKV_POOL_AVG = 1 } speckv_pool_op;
+
 #define SPECKV_MAX_SEQS 128     /* sequences per call                                        */
 #define SPECKV_MAX_GROUP_ROWS 4096 /* (n_q_heads / n_kv_heads) * R upper bound               */
 #define SPECKV_MAX_POOL_K 255
@@ -86,6 +98,8 @@ typedef struct {
   int64_t n_in;        /* used only when cu_seqlens == NULL                                  */
   int64_t q_stride_layer, q_stride_seq, q_stride_row, q_stride_head;
   int64_t kv_stride_layer, kv_stride_token, kv_stride_head;
+  int32_t reduce_op;   /* speckv_reduce_op; 0 (SUM) is the default                           */
+  int32_t pool_op;     /* speckv_pool_op; 0 (MAX) is the default                             */
 } speckv_params;
 
 /* Human-readable name of a status code (static storage). */

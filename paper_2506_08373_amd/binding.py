@@ -38,6 +38,7 @@ class _CParams(ctypes.Structure):
         ("q_stride_row", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
         ("kv_stride_layer", ctypes.c_int64), ("kv_stride_token", ctypes.c_int64),
         ("kv_stride_head", ctypes.c_int64),
+        ("reduce_op", ctypes.c_int32), ("pool_op", ctypes.c_int32),
     ]
 
 
@@ -94,7 +95,7 @@ class SpecKVParams:
 
     def __init__(self, *, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
                  seq_lens: Sequence[int], n_window: int, n_lookahead: int, pool_k: int, c_max: int,
-                 sm_scale: float, dtype: torch.dtype,
+                 sm_scale: float, dtype: torch.dtype, reduce: str = "sum", pool: str = "max",
                  q_strides: Optional[Tuple[int, int, int, int]] = None,
                  kv_strides: Optional[Tuple[int, int, int]] = None):
         self.seq_lens = [int(x) for x in seq_lens]
@@ -116,7 +117,8 @@ class SpecKVParams:
             cu_seqlens=ctypes.cast(self._cu, ctypes.POINTER(ctypes.c_int32)), n_in=0,
             q_stride_layer=q_strides[0], q_stride_seq=q_strides[1], q_stride_row=q_strides[2],
             q_stride_head=q_strides[3], kv_stride_layer=kv_strides[0], kv_stride_token=kv_strides[1],
-            kv_stride_head=kv_strides[2])
+            kv_stride_head=kv_strides[2], reduce_op={"sum": 0, "max": 1}[reduce],
+            pool_op={"max": 0, "avg": 1}[pool])
         self.torch_dtype = dtype
         self.n_layers, self.n_kv_heads, self.head_dim = n_layers, n_kv_heads, head_dim
         self.n_window, self.total_tokens = n_window, T
@@ -126,14 +128,15 @@ class SpecKVParams:
 
     @classmethod
     def for_tensors(cls, q: torch.Tensor, k: torch.Tensor, *, seq_lens, n_window, pool_k, c_max,
-                    sm_scale) -> "SpecKVParams":
+                    sm_scale, reduce: str = "sum", pool: str = "max") -> "SpecKVParams":
         """q [L, S, R, Hq, d], k [L, T, Hkv, d] (any strides with d contiguous)."""
         if q.dim() != 5 or k.dim() != 4 or q.stride(-1) != 1 or k.stride(-1) != 1:
             raise ValueError("expected q [L,S,R,Hq,d] and k [L,T,Hkv,d] with contiguous d")
         L, S, R, Hq, d = q.shape
         return cls(n_layers=L, n_q_heads=Hq, n_kv_heads=k.shape[2], head_dim=d, seq_lens=seq_lens,
                    n_window=n_window, n_lookahead=R - n_window, pool_k=pool_k, c_max=c_max,
-                   sm_scale=sm_scale, dtype=q.dtype, q_strides=tuple(q.stride()[:4]),
+                   sm_scale=sm_scale, dtype=q.dtype, reduce=reduce, pool=pool,
+                   q_strides=tuple(q.stride()[:4]),
                    kv_strides=tuple(k.stride()[:3]))
 
 

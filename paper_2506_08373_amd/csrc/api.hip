@@ -26,6 +26,8 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (p->pool_k < 1 || p->pool_k % 2 == 0 || p->c_max < 0) return SPECKV_ERR_INVALID_ARG;
   if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return SPECKV_ERR_INVALID_ARG;
   if (p->dtype != SPECKV_BF16 && p->dtype != SPECKV_F32) return SPECKV_ERR_INVALID_ARG;
+  if (p->reduce_op != SPECKV_REDUCE_SUM && p->reduce_op != SPECKV_REDUCE_MAX) return SPECKV_ERR_INVALID_ARG;
+  if (p->pool_op != SPECKV_POOL_MAX && p->pool_op != SPECKV_POOL_AVG) return SPECKV_ERR_INVALID_ARG;
   if (p->n_seqs > SPECKV_MAX_SEQS) return SPECKV_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return SPECKV_ERR_UNSUPPORTED;
   if (p->pool_k > SPECKV_MAX_POOL_K) return SPECKV_ERR_UNSUPPORTED;
@@ -35,6 +37,8 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   d.G = d.Hq / d.Hkv; d.D = p->head_dim; d.elt = p->dtype == SPECKV_BF16 ? 2 : 4;
   d.w = p->n_window; d.a = p->n_lookahead; d.R = d.w + d.a;
   d.pool_k = p->pool_k; d.c_max = p->c_max; d.sm_scale = p->sm_scale;
+  d.reduce_max = p->reduce_op == SPECKV_REDUCE_MAX; d.pool_avg = p->pool_op == SPECKV_POOL_AVG;
+  d.head_max = 0; d.weight_rows = 0;
   if ((int64_t)d.G * d.R > SPECKV_MAX_GROUP_ROWS) return SPECKV_ERR_UNSUPPORTED;
   d.M = d.G * d.R;
   d.q_sl = p->q_stride_layer; d.q_ss = p->q_stride_seq; d.q_sr = p->q_stride_row; d.q_sh = p->q_stride_head;
@@ -68,27 +72,41 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   d.T = t.cu[d.S];
   d.KT = t.ck[d.S];
 
-  // scoring geometry
+  // scoring geometry.  Every head's R rows are padded to Rp (a multiple of the 32-row MFMA block)
+  // so that no block mixes heads; (waves, blocks per wave): small groups use 4 waves, larger ones
+  // 8 waves so that two waves share each SIMD and the matrix and vector pipes overlap across them.
   ScoreGeom &g = pl->g;
-  // (waves, 32-row blocks per wave): small groups use 4 waves; larger ones 8 waves so that two
-  // waves share each SIMD and the matrix and vector pipes overlap across them.
-  if (d.M <= 128) { g.NW = 4; g.MB = 1; }
-  else if (d.M <= 256 || d.D * d.elt > 256) { g.NW = 8; g.MB = 1; }
+  g.Rp = (d.R + 31) / 32 * 32;
+  const int64_t m_pad = (int64_t)d.G * g.Rp;
+  if (m_pad <= 128) { g.NW = 4; g.MB = 1; }
+  else if (m_pad <= 256 || d.D * d.elt > 256) { g.NW = 8; g.MB = 1; }
   else { g.NW = 8; g.MB = 2; }
   g.RSB = g.NW * g.MB * 32;
-  g.RS = (d.M + g.RSB - 1) / g.RSB;
+  if (g.Rp <= g.RSB) {            // whole heads per super-block
+    g.HPS = g.RSB / g.Rp; g.PPH = 1; g.RS = (d.G + g.HPS - 1) / g.HPS;
+  } else {                        // one head spread over PPH super-blocks
+    g.HPS = 1; g.PPH = (g.Rp + g.RSB - 1) / g.RSB; g.RS = d.G * g.PPH;
+  }
   const int64_t units = (int64_t)d.L * d.Hkv * g.RS;
   if (units > 65535) return SPECKV_ERR_UNSUPPORTED;
+  // Keys [0, tail0) of a sequence are complete LDS tiles visible to every observation row
+  // (key <= m); they are cut into chunks of KC keys.  The rest is one masked tail chunk.
+  const int kt = d.D * d.elt <= 256 ? 128 : 64;
+  int64_t fast_keys = 0;
+  for (int s = 0; s < d.S; ++s) {
+    const int n_s = t.cu[s + 1] - t.cu[s];
+    const int visible_to_all = n_s - d.w + 1 < n_s ? n_s - d.w + 1 : n_s;    // keys 0..m, clipped
+    t.tail0[s] = visible_to_all / kt * kt;
+    fast_keys += t.tail0[s];
+  }
   const int64_t want_chunks = (kTargetWorkgroups + units - 1) / units;
-  int64_t kc = align_up((d.T + want_chunks - 1) / want_chunks, kChunkAlign);
+  int64_t kc = align_up((fast_keys + want_chunks - 1) / want_chunks, kChunkAlign);
   if (kc < 4 * kChunkAlign) kc = 4 * kChunkAlign;
   g.KC = (int32_t)kc;
   t.cc[0] = 0;
-  for (int s = 0; s < d.S; ++s) {
-    const int n_s = t.cu[s + 1] - t.cu[s];
-    t.cc[s + 1] = t.cc[s] + (n_s + g.KC - 1) / g.KC;
-  }
-  g.n_chunks = t.cc[d.S];
+  for (int s = 0; s < d.S; ++s) t.cc[s + 1] = t.cc[s] + (t.tail0[s] + g.KC - 1) / g.KC;
+  g.n_fast_chunks = t.cc[d.S];
+  g.n_chunks = g.n_fast_chunks + d.S;
 
   // workspace carve-up
   size_t off = 0;

@@ -58,6 +58,12 @@ struct ScoreArgs {
   float *planes;    // [RS][layer][Hkv*T]
 };
 
+__device__ inline float max_other_half(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int ELT>
 __device__ inline f32x16 mma_chunk(u32x4 a, u32x4 b, f32x16 acc);
 
@@ -88,13 +94,19 @@ struct Tile {
   __device__ static inline int swizzle(int row) { return (row / RPB) & SWZ; }
 };
 
-template <int ELT, int D, int NW>
+template <int ELT, int D, int MB, int NW>
 constexpr size_t score_lds_bytes() {
   using TL = Tile<ELT, D>;
-  return (size_t)2 * TL::TILE_BYTES + (size_t)2 * NW * TL::KT * sizeof(float);
+  return (size_t)2 * TL::TILE_BYTES + (size_t)2 * NW * MB * TL::KT * sizeof(float);
 }
 
-template <int ELT, int D, int MB, int NW, int PASS>
+// One sweep over a chunk of keys.
+//   PASS    1: row statistics, 2: column reduction
+//   RED     (pass 2) 0: sum over the rows of a head, 1: max over the rows of a head
+//   MASKED  false: every tile of the chunk is complete and visible to every row (key <= m), the
+//           loop body is straight-line code without any bounds or mask logic;
+//           true: the tail of a sequence (keys that window rows may not see, end of sequence)
+template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
 __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   using TL = Tile<ELT, D>;
   constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
@@ -109,17 +121,25 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   const Dims &d = A.d;
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int chunk = blockIdx.x;
   const int unit = blockIdx.y;
   const int rs = unit % A.g.RS;
   const int g = (unit / A.g.RS) % d.Hkv;
   const int layer = unit / (A.g.RS * d.Hkv);
-  int s = 0;
-  while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
+  int s, chunk, key_begin, key_end;
+  if (MASKED) {
+    s = blockIdx.x;
+    chunk = A.g.n_fast_chunks + s;
+    key_begin = A.t.tail0[s];
+    key_end = A.t.cu[s + 1] - A.t.cu[s];
+  } else {
+    chunk = blockIdx.x;
+    s = 0;
+    while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
+    key_begin = (chunk - A.t.cc[s]) * A.g.KC;
+    key_end = min(A.t.tail0[s], key_begin + A.g.KC);
+  }
   const int n_s = A.t.cu[s + 1] - A.t.cu[s];
   const int m = n_s - d.w;
-  const int key_begin = (chunk - A.t.cc[s]) * A.g.KC;
-  const int key_end = min(n_s, key_begin + A.g.KC);
   const int ntiles = (key_end - key_begin + KT - 1) / KT;
   const float c2 = d.sm_scale * 1.4426950408889634f;
 
@@ -127,11 +147,10 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   u32x4 qf[MB][NCS];
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
-    const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
-    const bool valid = row < d.M;
-    const int hh = valid ? row / d.R : 0, i = valid ? row % d.R : 0;
-    const char *qp = A.q + ((int64_t)layer * d.q_sl + (int64_t)s * d.q_ss + (int64_t)i * d.q_sr +
-                            (int64_t)(g * d.G + hh) * d.q_sh) * ELT + (half * NCS) * 16;
+    int hh, i;
+    const bool valid = decode_row(d, A.g, rs, (wv * MB + rb) * 32 + l32, &hh, &i);
+    const char *qp = A.q + ((int64_t)layer * d.q_sl + (int64_t)s * d.q_ss + (int64_t)(valid ? i : 0) * d.q_sr +
+                            (int64_t)(g * d.G + (valid ? hh : 0)) * d.q_sh) * ELT + (half * NCS) * 16;
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs)
       qf[rb][cs] = valid ? *reinterpret_cast<const u32x4 *>(qp + cs * 16) : (u32x4)(0u);
@@ -149,9 +168,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-        const float v = lp[row];                            // the lse buffer covers the padded rows
-        nlse[rb][i] = row < d.M ? -v : -INFINITY;           // padded rows contribute 2^-inf = 0
+        const int lr = (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+        int hh, io;
+        const bool valid = decode_row(d, A.g, rs, lr, &hh, &io);
+        float v = -lp[rs * RSB + lr];                       // the lse buffer covers the padded rows
+        if (d.weight_rows && io < d.w) v += log2f((float)(io + 1) / (float)d.w);   // row weight folded in
+        nlse[rb][i] = valid ? v : -INFINITY;                // padded rows contribute 2^-inf = 0
       }
   }
 
@@ -167,7 +189,8 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
       const int seg_ = it * NW + wv;                                                          \
       const int r_ = seg_ * RPS + st_row;                                                     \
       const int c_ = st_slot ^ TL::swizzle(r_);                                               \
-      const int key_ = min(k0_ + r_, n_s - 1); /* tail rows re-read the last key; masked */   \
+      /* rows past the end of the sequence re-read its last key; they are masked later */     \
+      const int key_ = MASKED ? min(k0_ + r_, n_s - 1) : k0_ + r_;                            \
       __builtin_amdgcn_global_load_lds(                                                       \
           (const __attribute__((address_space(1))) void *)(kbase + (int64_t)key_ * tokb + c_ * 16),   \
           (__attribute__((address_space(3))) void *)(kbuf + (buf_) * TILE_BYTES + seg_ * 1024), 16, 0, 0); \
@@ -181,23 +204,40 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   _Pragma("unroll") for (int cs = 0; cs < NCS; ++cs)                                          \
     dst_[cs] = *reinterpret_cast<const u32x4 *>(kbuf + (buf_) * TILE_BYTES + (kb_) * 32 * ROWB + foff[cs]);
 
-  // cross-wave column-sum reduction of one finished tile (pass 2)
+  // cross-wave merge of the column partials of one finished tile (pass 2)
   float *plane_out = nullptr;
   if (PASS == 2)
     plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s;
+  const int blocks_per_head = (A.g.PPH == 1 ? A.g.Rp : RSB) / 32;
+  const bool head_max = d.head_max != 0;
 #define SPECKV_FLUSH_TILE(tile_)                                                             \
   if (tid < KT) {                                                                            \
     const int key_ = key_begin + (tile_) * KT + tid;                                         \
     if (key_ < key_end) {                                                                    \
-      const float *cp_ = csum + (size_t)((tile_) & 1) * NW * KT + tid;                       \
-      float sum_ = 0.f;                                                                      \
-      _Pragma("unroll") for (int w2 = 0; w2 < NW; ++w2) sum_ += cp_[w2 * KT];                \
-      plane_out[key_] = sum_;                                                                \
+      const float *cp_ = csum + (size_t)((tile_) & 1) * NW * MB * KT + tid;                  \
+      float total_ = 0.f;                                                                    \
+      if (RED == 0) {                                                                        \
+        _Pragma("unroll") for (int w2 = 0; w2 < NW; ++w2) total_ += cp_[w2 * KT];            \
+      } else {                                                                               \
+        /* per 32-row block maxima: max within a head, then heads added (or maxed) */        \
+        float cur_ = 0.f;                                                                    \
+        _Pragma("unroll") for (int b2 = 0; b2 < NW * MB; ++b2) {                             \
+          if (b2 > 0 && b2 % blocks_per_head == 0) {                                         \
+            total_ = head_max ? fmaxf(total_, cur_) : total_ + cur_;                         \
+            cur_ = 0.f;                                                                      \
+          }                                                                                  \
+          cur_ = fmaxf(cur_, cp_[b2 * KT]);                                                  \
+        }                                                                                    \
+        total_ = head_max ? fmaxf(total_, cur_) : total_ + cur_;                             \
+      }                                                                                      \
+      plane_out[key_] = total_;                                                              \
     }                                                                                        \
   }
 
-  SPECKV_LOAD_TILE(0, 0)
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (ntiles > 0) {
+    SPECKV_LOAD_TILE(0, 0)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
   __syncthreads();
 
   for (int tile = 0; tile < ntiles; ++tile) {
@@ -205,8 +245,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
     if (tile + 1 < ntiles) SPECKV_LOAD_TILE(tile + 1, buf ^ 1)
     if (PASS == 2 && tile > 0) SPECKV_FLUSH_TILE(tile - 1)
     const int tk0 = key_begin + tile * KT;
-    if (tk0 + KT <= key_end && tk0 + KT <= m + 1) {
-      // Fast path: every key of the tile exists and is visible to every row (key <= m).
+    if (!MASKED) {
       // Per 32-key block the MB accumulator chains of this wave are interleaved MFMA by MFMA
       // (no back-to-back dependent MFMAs); the fragments of the next block are fetched while
       // the vector pipe turns the scores into probabilities.  The second wave on the SIMD
@@ -242,11 +281,12 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
             mrun[rb] = mnew;
           }
         } else {
-          // probabilities in batches of 8: all multiply-adds, then all exp2, then the adds, so
-          // that no instruction waits on the transcendental issued just before it
+          // probabilities in batches of 8: all multiply-adds, then all exp2, then the reduction,
+          // so that no instruction waits on the transcendental issued just before it
           float colsum = 0.f;
 #pragma unroll
-          for (int rb = 0; rb < MB; ++rb)
+          for (int rb = 0; rb < MB; ++rb) {
+            if (RED == 1) colsum = 0.f;
 #pragma unroll
             for (int h8 = 0; h8 < 16; h8 += 8) {
               float x[8];
@@ -255,23 +295,33 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
               for (int i = 0; i < 8; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
               __builtin_amdgcn_sched_barrier(0);
+              if (RED == 0) {
 #pragma unroll
-              for (int i = 0; i < 8; ++i) colsum += x[i];
+                for (int i = 0; i < 8; ++i) colsum += x[i];
+              } else {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) colsum = fmaxf(fmaxf(colsum, x[i]), x[i + 1]);
+              }
               __builtin_amdgcn_sched_barrier(0);
             }
-          colsum = add_other_half(colsum);
-          if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
+            if (RED == 1) {        // one value per 32-row block: blocks of a head are merged at the flush
+              colsum = max_other_half(colsum);
+              if (half == 0) csum[(size_t)buf * NW * MB * KT + (wv * MB + rb) * KT + kb * 32 + l32] = colsum;
+            }
+          }
+          if (RED == 0) {
+            colsum = add_other_half(colsum);
+            if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
+          }
         }
       }
     } else {
-      // Slow path (tiles that touch the window or the end of the sequence): masks applied.
+      // Tail tiles: keys above m are hidden from some window rows; keys >= n_s do not exist.
 #pragma unroll 1
       for (int kb = 0; kb < KT / 32; ++kb) {
         if (tk0 + kb * 32 >= key_end) break;               // nothing but padding from here on
         u32x4 bf[NCS];
         SPECKV_LOAD_BFRAG(bf, buf, kb)
-        // keys above m are hidden from some window rows; keys >= n_s do not exist
-        const bool need_mask = tk0 + (kb + 1) * 32 > m;
         if (PASS == 1) {
 #pragma unroll
           for (int rb = 0; rb < MB; ++rb) {
@@ -279,15 +329,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
             for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
             // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
-            if (need_mask) {
-              const int row = rs * RSB + (wv * MB + rb) * 32 + l32;
-              const int iobs = row % d.R;
-              const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
+            int hh_, iobs;
+            decode_row(d, A.g, rs, (wv * MB + rb) * 32 + l32, &hh_, &iobs);
+            const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                if (key > last) acc[i] = -INFINITY;
-              }
+            for (int i = 0; i < 16; ++i) {
+              const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+              if (key > last) acc[i] = -INFINITY;
             }
             float tmax = acc[0];
 #pragma unroll
@@ -313,20 +361,28 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
             float p[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nlse[rb][i]));
-            if (need_mask) {
 #pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int row = rs * RSB + (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                const int iobs = row % d.R;
-                const int last = iobs < d.w ? m + iobs : n_s - 1;
-                if (key > last) p[i] = 0.f;
-              }
+            for (int i = 0; i < 16; ++i) {
+              int hh_, iobs;
+              decode_row(d, A.g, rs, (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3), &hh_, &iobs);
+              const int last = iobs < d.w ? m + iobs : n_s - 1;
+              if (key > last) p[i] = 0.f;
             }
+            if (RED == 0) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) colsum += p[i];
+              for (int i = 0; i < 16; ++i) colsum += p[i];
+            } else {
+              float cm = 0.f;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) cm = fmaxf(cm, p[i]);
+              cm = max_other_half(cm);
+              if (half == 0) csum[(size_t)buf * NW * MB * KT + (wv * MB + rb) * KT + kb * 32 + l32] = cm;
+            }
           }
-          colsum = add_other_half(colsum);
-          if (half == 0) csum[(size_t)buf * NW * KT + wv * KT + kb * 32 + l32] = colsum;
+          if (RED == 0) {
+            colsum = add_other_half(colsum);
+            if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
+          }
         }
       }
     }
@@ -336,6 +392,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   }
 
   if (PASS == 1) {
+    // an empty chunk (a sequence without masked tail) leaves the neutral pair (-big, 0)
     float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks + chunk) * RSB;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
@@ -344,7 +401,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
       const float ll = lrun[rb] * __builtin_amdgcn_exp2f(mrun[rb] - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
       if (half == 0) pp[(wv * MB + rb) * 32 + l32] = make_float2(mm, ll);
     }
-  } else {
+  } else if (ntiles > 0) {
     SPECKV_FLUSH_TILE(ntiles - 1)
   }
 }
@@ -382,6 +439,10 @@ __global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(
     const float2 v = pp[(int64_t)c * RSB];
     merge_pair(mm, ll, v.x, v.y);
   }
+  if (slice == 0) {                                   // the sequence's masked tail chunk
+    const float2 v = pp[(int64_t)(A.g.n_fast_chunks + s) * RSB];
+    merge_pair(mm, ll, v.x, v.y);
+  }
   partial[slice][threadIdx.x % kMergeRows] = make_float2(mm, ll);
   __syncthreads();
   if (slice == 0) {
@@ -394,27 +455,40 @@ __global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(
   }
 }
 
+template <typename K>
+hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, grid, block, lds, st, A);
+  return hipGetLastError();
+}
+
+template <int ELT, int D, int MB, int NW, int PASS, int RED>
+hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
+  const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
+  hipError_t e;
+  if (A.g.n_fast_chunks > 0) {
+    e = launch_one(score_kernel<ELT, D, MB, NW, PASS, RED, false>, A, dim3(A.g.n_fast_chunks, units),
+                   dim3(NW * 64), lds, st);
+    if (e != hipSuccess) return e;
+  }
+  return launch_one(score_kernel<ELT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
+}
+
 template <int ELT, int D, int MB, int NW>
 hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
-  const size_t lds = score_lds_bytes<ELT, D, NW>();
-  auto k1 = score_kernel<ELT, D, MB, NW, 1>;
-  auto k2 = score_kernel<ELT, D, MB, NW, 2>;
+  const size_t lds = score_lds_bytes<ELT, D, MB, NW>();
   hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  const dim3 grid(A.g.n_chunks, A.d.L * A.d.Hkv * A.g.RS), block(NW * 64);
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k1, grid, block, lds, st, A);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_sweep<ELT, D, MB, NW, 1, 0>(A, lds, st)) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
   hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS * (A.g.RSB / kMergeRows), A.d.S),
                      dim3(kMergeRows * kMergeSlices), 0, st, A);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
-  hipLaunchKernelGGL(k2, grid, block, lds, st, A);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  e = A.d.reduce_max ? launch_sweep<ELT, D, MB, NW, 2, 1>(A, lds, st) : launch_sweep<ELT, D, MB, NW, 2, 0>(A, lds, st);
+  if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
   return hipSuccess;
 }

@@ -21,18 +21,33 @@ namespace {
 constexpr int kPoolThreads = 256;
 constexpr int kPoolTile = 1024;
 
-// Sums n_planes values per key, writes raw (optional) and pooled for one row tile.
-__device__ inline void reduce_pool_tile(const float *__restrict__ in, int n_planes,
-                                        int64_t plane_stride, float *__restrict__ raw,
-                                        float *__restrict__ pooled, int n_s, int m, int half,
-                                        int j0, float *tile) {
+// How the partial planes of one output row are merged: value = outer over groups of
+// (inner over the n_inner consecutive planes of a group); each op is a sum or a max.
+struct PlaneMerge {
+  int n_outer, n_inner;
+  int inner_max, outer_max;
+  int64_t plane_stride;
+};
+
+// Merges the planes per key, writes raw (optional) and pooled for one row tile.
+__device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge pm,
+                                        float *__restrict__ raw, float *__restrict__ pooled,
+                                        int n_s, int m, int pool_k, int pool_avg, int j0, float *tile) {
+  const int half = pool_k / 2;
   const int span = kPoolTile + 2 * half;
   for (int x = threadIdx.x; x < span; x += kPoolThreads) {
     const int jj = j0 - half + x;
     float acc = 0.f;
     if (jj >= 0 && jj < n_s) {
       const float *p = in + jj;
-      for (int pl = 0; pl < n_planes; ++pl) acc += p[pl * plane_stride];
+      for (int o = 0; o < pm.n_outer; ++o) {
+        float v = 0.f;                                   // scores are non-negative: 0 is neutral for max
+        for (int q = 0; q < pm.n_inner; ++q) {
+          const float y = p[(int64_t)(o * pm.n_inner + q) * pm.plane_stride];
+          v = pm.inner_max ? fmaxf(v, y) : v + y;
+        }
+        acc = pm.outer_max ? fmaxf(acc, v) : acc + v;
+      }
     }
     tile[x] = acc;
   }
@@ -46,14 +61,19 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, int n_plan
     if (j < m) {
       const int lo = max(0, j - half), hi = min(m - 1, j + half);
       best = tile[lo - j0 + half];
-      for (int jj = lo + 1; jj <= hi; ++jj) best = fmaxf(best, tile[jj - j0 + half]);
+      if (pool_avg) {
+        for (int jj = lo + 1; jj <= hi; ++jj) best += tile[jj - j0 + half];
+        best /= (float)pool_k;                            // zeros outside [0, m) count in the divisor
+      } else {
+        for (int jj = lo + 1; jj <= hi; ++jj) best = fmaxf(best, tile[jj - j0 + half]);
+      }
     }
     pooled[j] = best;
   }
 }
 
 __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
-    Dims d, SeqTab t, int n_planes, int64_t plane_stride, const float *__restrict__ planes,
+    Dims d, SeqTab t, PlaneMerge pm, const float *__restrict__ planes,
     float *__restrict__ raw, float *__restrict__ pooled, int tiles_per_row) {
   __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
   const int unit = blockIdx.x / tiles_per_row;
@@ -64,20 +84,19 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
   const int n_s = t.cu[s + 1] - t.cu[s];
   if (j0 >= n_s) return;
   const int64_t base = (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
-  reduce_pool_tile(planes + base, n_planes, plane_stride, raw ? raw + base : nullptr,
-                   pooled + base, n_s, n_s - d.w, d.pool_k / 2, j0, tile);
+  reduce_pool_tile(planes + base, pm, raw ? raw + base : nullptr, pooled + base, n_s, n_s - d.w,
+                   d.pool_k, d.pool_avg, j0, tile);
 }
 
-// One output row that sums every plane (all layers, heads, row super-blocks) of a
+// One output row that merges every plane (all layers, heads, row super-blocks) of a
 // single-sequence call: planes are consecutive rows of n_in floats.
 __global__ __launch_bounds__(kPoolThreads) void reduce_pool_all_kernel(
-    int n_in, int n_window, int pool_k, int n_planes, const float *__restrict__ planes,
+    int n_in, int n_window, int pool_k, int pool_avg, PlaneMerge pm, const float *__restrict__ planes,
     float *__restrict__ raw, float *__restrict__ pooled) {
   __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
   const int j0 = blockIdx.x * kPoolTile;
   if (j0 >= n_in) return;
-  reduce_pool_tile(planes, n_planes, (int64_t)n_in, raw, pooled, n_in, n_in - n_window,
-                   pool_k / 2, j0, tile);
+  reduce_pool_tile(planes, pm, raw, pooled, n_in, n_in - n_window, pool_k, pool_avg, j0, tile);
 }
 
 // ----------------------------------------------------------------------------------
@@ -267,8 +286,15 @@ hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, f
   for (int s = 0; s < d.S; ++s) max_n = max(max_n, pl.t.cu[s + 1] - pl.t.cu[s]);
   const int tiles = (max_n + kPoolTile - 1) / kPoolTile;
   const int64_t blocks = (int64_t)d.L * d.S * d.Hkv * tiles;
+  // planes of one head (PPH slices) merge like the rows of a head; heads merge by sum or max
+  PlaneMerge pm;
+  pm.n_inner = pl.g.PPH;
+  pm.n_outer = pl.g.RS / pl.g.PPH;
+  pm.inner_max = d.reduce_max;
+  pm.outer_max = d.reduce_max && d.head_max;
+  pm.plane_stride = (int64_t)d.L * d.Hkv * d.T;
   hipLaunchKernelGGL(reduce_pool_kernel, dim3((unsigned)blocks), dim3(kPoolThreads), 0, st, d, pl.t,
-                     pl.g.RS, (int64_t)d.L * d.Hkv * d.T, planes, raw, pooled, tiles);
+                     pm, planes, raw, pooled, tiles);
   return hipGetLastError();
 }
 
@@ -277,8 +303,15 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
   const Dims &d = pl.d;
   const int n_in = (int)d.T;
   const int tiles = (n_in + kPoolTile - 1) / kPoolTile;
+  // every plane (row super-block, layer, head) merges with one op: all sums, or all maxima
+  PlaneMerge pm;
+  pm.n_inner = 1;
+  pm.n_outer = pl.g.RS * d.L * d.Hkv;
+  pm.inner_max = 0;
+  pm.outer_max = d.reduce_max && d.head_max;
+  pm.plane_stride = n_in;
   hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kPoolThreads), 0, st, n_in, d.w,
-                     d.pool_k, pl.g.RS * d.L * d.Hkv, planes, raw, pooled);
+                     d.pool_k, d.pool_avg, pm, planes, raw, pooled);
   return hipGetLastError();
 }
 

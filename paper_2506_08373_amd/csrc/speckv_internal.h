@@ -16,13 +16,18 @@ struct SeqTab {
   int32_t n_seqs;
   int32_t cu[kMaxSeqs + 1];   // token prefix sums
   int32_t ck[kMaxSeqs + 1];   // prefix sums of n_keep_s
-  int32_t cc[kMaxSeqs + 1];   // prefix sums of key chunks (scoring grid)
+  int32_t cc[kMaxSeqs + 1];   // prefix sums of the unmasked key chunks (scoring grid)
+  int32_t tail0[kMaxSeqs];    // first key of the masked tail: keys below it are visible to every row
 };
 
 struct Dims {
   int32_t L, S, Hq, Hkv, G, D, elt;       // elt = bytes per element (2 bf16, 4 f32)
   int32_t w, a, R, M;                      // M = G * R rows per KV group
   int32_t pool_k, c_max;
+  int32_t reduce_max;                      // 1: max over the rows of a head instead of the sum
+  int32_t head_max;                        // 1: heads (and layers) combined by max instead of sum
+  int32_t pool_avg;                        // 1: zero-padded mean instead of the clipped max
+  int32_t weight_rows;                     // 1: window row i scaled by (i + 1) / n_window (Alg. 2)
   float sm_scale;
   int64_t q_sl, q_ss, q_sr, q_sh;          // element strides
   int64_t kv_sl, kv_st, kv_sh;
@@ -34,9 +39,13 @@ struct ScoreGeom {
   int32_t MB;         // 32-row blocks per wave
   int32_t NW;         // waves per workgroup
   int32_t RSB;        // rows per workgroup = NW * MB * 32
-  int32_t RS;         // row super-blocks per KV group = ceil(M / RSB)
+  int32_t RS;         // row super-blocks per KV group
+  int32_t Rp;         // observation rows per head, padded to a multiple of 32
+  int32_t HPS;        // whole heads per super-block (when a head fits), else 1
+  int32_t PPH;        // super-blocks per head (1 when a head fits)
   int32_t KC;         // keys per chunk (multiple of the LDS tile)
-  int32_t n_chunks;   // total chunks over all sequences = cc[S]
+  int32_t n_fast_chunks;   // unmasked chunks over all sequences = cc[S]
+  int32_t n_chunks;        // n_fast_chunks + one masked tail chunk per sequence
 };
 
 struct Plan {
@@ -56,6 +65,20 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const in
 // row statistics, before pass 2 and after pass 2.
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
                         float *planes, hipStream_t st, hipEvent_t *events = nullptr);
+// Row `lr` of super-block `rs` -> (head in group, observation row); false for padding rows.
+// Heads never share a 32-row block: each head's R rows are padded to Rp, and a super-block holds
+// either HPS whole heads or one of the PPH slices of a single head.
+__host__ __device__ inline bool decode_row(const Dims &d, const ScoreGeom &g, int rs, int lr, int *hh, int *i) {
+  if (g.PPH == 1) {
+    *hh = rs * g.HPS + lr / g.Rp;
+    *i = lr % g.Rp;
+    return lr < g.HPS * g.Rp && *hh < d.G && *i < d.R;
+  }
+  *hh = rs / g.PPH;
+  *i = (rs % g.PPH) * g.RSB + lr;
+  return *i < d.R;
+}
+
 // out rows = (layer, seq, head): pooled/raw in the "scores" layout from RS planes.
 hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
                               hipStream_t st);

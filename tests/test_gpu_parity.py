@@ -30,28 +30,28 @@ def S():
     return lib
 
 
-def make_params(S, w, c_max=None, pool_k=None, q=None, k=None):
+def make_params(S, w, c_max=None, pool_k=None, q=None, k=None, reduce="sum", pool="max"):
     if q is not None:
         return S.SpecKVParams.for_tensors(q, k, seq_lens=w.seq_lens, n_window=w.n_window,
                                           pool_k=w.pool_k if pool_k is None else pool_k,
                                           c_max=w.c_max if c_max is None else c_max,
-                                          sm_scale=w.sm_scale)
+                                          sm_scale=w.sm_scale, reduce=reduce, pool=pool)
     return S.SpecKVParams(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
                           head_dim=w.head_dim, seq_lens=w.seq_lens, n_window=w.n_window,
                           n_lookahead=w.n_lookahead, pool_k=w.pool_k if pool_k is None else pool_k,
                           c_max=w.c_max if c_max is None else c_max, sm_scale=w.sm_scale,
-                          dtype=w.torch_dtype)
+                          dtype=w.torch_dtype, reduce=reduce, pool=pool)
 
 
 def alloc_ws(S, p):
     return torch.empty(max(S.workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
 
 
-def oracle_batch(w, t, c_max=None, pool_k=None):
+def oracle_batch(w, t, c_max=None, pool_k=None, reduce="sum", pool="max"):
     q, k, v = (workloads.to_float64(t[x]) for x in ("q", "k", "v"))
     return orc.speckv_batch(q, k, v, w.cu_seqlens, w.n_window,
                             w.pool_k if pool_k is None else pool_k,
-                            w.c_max if c_max is None else c_max, w.sm_scale)
+                            w.c_max if c_max is None else c_max, w.sm_scale, reduce=reduce, pool=pool)
 
 
 def split_scores(w, flat, layer, s):
@@ -104,8 +104,8 @@ def assert_indices_valid(idx_row, pooled_ref_row, n, w_, c_max, what):
     return False
 
 
-def run_compress(S, w, t_gpu, c_max=None, pool_k=None):
-    p = make_params(S, w, c_max=c_max, pool_k=pool_k)
+def run_compress(S, w, t_gpu, c_max=None, pool_k=None, reduce="sum", pool="max"):
+    p = make_params(S, w, c_max=c_max, pool_k=pool_k, reduce=reduce, pool=pool)
     KT = S.total_keep(p)
     L, H, d = w.n_layers, w.n_kv_heads, w.head_dim
     idx = torch.full((L, H * KT), -7, dtype=torch.int32, device="cuda")
@@ -117,14 +117,14 @@ def run_compress(S, w, t_gpu, c_max=None, pool_k=None):
     return p, idx.cpu().numpy(), k_out.cpu(), v_out.cpu()
 
 
-def check_full_path(S, w, c_max=None, pool_k=None, expect_exact=None):
+def check_full_path(S, w, c_max=None, pool_k=None, expect_exact=None, reduce="sum", pool="max"):
     c_eff = w.c_max if c_max is None else c_max
     t = workloads.generate(w)
     tg = {x: t[x].cuda() for x in ("q", "k", "v")}
-    ref = oracle_batch(w, t, c_max=c_max, pool_k=pool_k)
+    ref = oracle_batch(w, t, c_max=c_max, pool_k=pool_k, reduce=reduce, pool=pool)
 
     # --- scores
-    p = make_params(S, w, c_max=c_max, pool_k=pool_k)
+    p = make_params(S, w, c_max=c_max, pool_k=pool_k, reduce=reduce, pool=pool)
     L, H, T = w.n_layers, w.n_kv_heads, w.total_tokens
     pooled = torch.full((L, H * T), -1.0, dtype=torch.float32, device="cuda")
     raw = torch.full((L, H * T), -1.0, dtype=torch.float32, device="cuda")
@@ -143,7 +143,7 @@ def check_full_path(S, w, c_max=None, pool_k=None, expect_exact=None):
             assert (got_p[:, m:] == 0).all()
 
     # --- fused path: indices and compacted cache
-    _, idx_h, k_out, v_out = run_compress(S, w, tg, c_max=c_max, pool_k=pool_k)
+    _, idx_h, k_out, v_out = run_compress(S, w, tg, c_max=c_max, pool_k=pool_k, reduce=reduce, pool=pool)
     exact = 0
     total = 0
     cu = w.cu_seqlens
@@ -221,6 +221,35 @@ def test_fp32_head_dim_128_and_group_1(S):
         n_window=8, n_lookahead=24, pool_k=5, c_max=64, dtype="f32", sm_scale=1 / math.sqrt(128),
         n_planted=4, channel_scale=None, seed=22)
     check_full_path(S, w, expect_exact=1.0)
+
+
+# ------------------------------------------------------------------ the listing's setting
+@pytest.mark.parametrize("reduce,pool", [("max", "max"), ("max", "avg"), ("sum", "avg")])
+def test_max_reduction_and_average_pooling_llama_shape(S, reduce, pool):
+    """Alg. 1 as printed: max over the observation rows of a head, average pooling."""
+    w = workloads.llama8b_layer(n_in=4096 + 300, c_max=512, name="c2_maxavg")
+    check_full_path(S, w, reduce=reduce, pool=pool)
+
+
+def test_max_reduction_ragged_gqa7_and_tiny(S):
+    w = workloads.ragged_batch(n_layers=2, lo=150, hi=1500, n_seqs=3, seed=9, name="c4_max")
+    check_full_path(S, w, c_max=100, reduce="max", pool="avg")
+    check_full_path(S, workloads.tiny_fp32(), reduce="max", pool="max")
+
+
+@pytest.mark.parametrize("n_window,n_lookahead,G", [
+    (32, 64, 4),      # the paper's window with 64 draft tokens: 96 rows per head
+    (5, 8, 3),        # rows per head far from a multiple of 32
+    (64, 500, 2),     # a head larger than one workgroup's 512 rows
+    (0, 1, 8),        # a single row per head
+])
+@pytest.mark.parametrize("reduce", ["sum", "max"])
+def test_row_layouts(S, n_window, n_lookahead, G, reduce):
+    w = workloads.SpecKVWorkload(
+        name="rows", n_layers=1, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, seq_lens=(777,),
+        n_window=n_window, n_lookahead=n_lookahead, pool_k=7, c_max=60, dtype="bf16",
+        sm_scale=1 / math.sqrt(128), n_planted=4, channel_scale=(0.5, 4.0), seed=23)
+    check_full_path(S, w, reduce=reduce)
 
 
 def test_strided_inputs(S):
