@@ -262,3 +262,37 @@ def specpc_select_tokens(q: np.ndarray, k: np.ndarray, token_ids: np.ndarray, n_
     idx = expand_neighbors(sel, n, n_window, n_neighbor)
     return {"raw": raw, "pooled": pooled, "sel": sel, "idx": idx,
             "ids": np.asarray(token_ids)[idx], "count": np.int64(idx.shape[0])}
+
+
+def specpc_window_weights(n_window: int, n_rows: int) -> np.ndarray:
+    """Row weights of Alg. 2: the j-th window row (1-based) gets j / n_window, later rows 1."""
+    wts = np.ones(n_rows, dtype=np.float64)
+    wts[:n_window] = (np.arange(n_window) + 1.0) / n_window
+    return wts
+
+
+def specpc_compress_prompt(q: np.ndarray, k: np.ndarray, token_ids: np.ndarray, n_window: int,
+                           pool_k: int, n_neighbor: int, c_max: int, l_skip: int,
+                           sm_scale: float) -> Dict[str, np.ndarray]:
+    """Prompt compression of Sec. 4.2 / Alg. 2 on draft-model queries and keys.
+
+    q [L, R, Hq, d] (window rows first, then the lookahead rows), k [L, n, Hkv, d].  The first
+    l_skip layers are ignored; window row j is weighted j / n_window; the weighted probabilities
+    are max-reduced over layers, heads and rows; AvgPool1D(pool_k) then MaxPool1D(n_neighbor)
+    (both odd here, zero / clipped padding as in avg_pool_1d / max_pool_1d); the top c_max
+    non-window tokens plus the window are kept, ascending.
+    """
+    n = k.shape[1]
+    m = n - n_window
+    wts = specpc_window_weights(n_window, q.shape[1])
+    raw = np.zeros(n, dtype=np.float64)
+    for layer in range(l_skip, q.shape[0]):
+        per_head = raw_scores(q[layer], k[layer], n_window, sm_scale, reduce="max", row_weights=wts,
+                              head_reduce="max")
+        raw = np.maximum(raw, per_head.max(axis=0))
+    smooth = avg_pool_1d(raw[:m], pool_k)
+    spread = max_pool_1d(smooth, n_neighbor)
+    sel = select_top(spread, min(c_max, m))
+    idx = np.concatenate([sel, np.arange(m, n, dtype=np.int64)])
+    return {"raw": raw, "smooth": smooth, "pooled": spread, "sel": sel, "idx": idx,
+            "ids": np.asarray(token_ids)[idx], "count": np.int64(idx.shape[0])}

@@ -442,3 +442,41 @@ def test_paper_setting_end_to_end_vs_brute_force():
             want = bf.speckv_layer(q.tolist(), k.tolist(), v.tolist(), w, 5, 4, 0.9, reduce, pool)
             np.testing.assert_allclose(got["pooled"], np.array(want["pooled"]).reshape(Hkv, n - w), rtol=1e-11, atol=1e-15)
             assert got["idx"].tolist() == want["idx"]
+
+
+# ------------------------------------------------------------------ prompt compression (Alg. 2)
+def test_specpc_alg2_matches_library_composition():
+    w = workloads.specpc_draft(n_in=300, n_layers=4, name="c5_alg2")
+    w = workloads.SpecKVWorkload(**{**w.__dict__, "n_lookahead": 2})
+    t = workloads.generate(w)
+    ids = workloads.generate_token_ids(w, vocab=5000)
+    q, k = workloads.to_float64(t["q"][:, 0]), workloads.to_float64(t["k"])
+    n, nw, l_skip, pk, nn, cm = 300, w.n_window, 1, 5, 9, 40
+    res = orc.specpc_compress_prompt(q, k, ids.numpy(), nw, pk, nn, cm, l_skip, w.sm_scale)
+    # library route: stack the weighted probabilities and take one amax over layers, heads, rows
+    m = n - nw
+    G = w.group
+    tq, tk = torch.from_numpy(q), torch.from_numpy(k)
+    wts = torch.ones(w.n_rows, dtype=torch.float64)
+    wts[:nw] = (torch.arange(nw, dtype=torch.float64) + 1) / nw          # j / n_window, j = 1..n_window
+    best = torch.zeros(n, dtype=torch.float64)
+    for layer in range(l_skip, w.n_layers):
+        for h in range(w.n_q_heads):
+            logits = torch.einsum("id,jd->ij", tq[layer, :, h], tk[layer, :, h // G]) * w.sm_scale
+            for i in range(nw):
+                logits[i, m + i + 1:] = float("-inf")
+            best = torch.maximum(best, (torch.softmax(logits, 1) * wts[:, None]).amax(0))
+    np.testing.assert_allclose(res["raw"], best.numpy(), rtol=1e-12)
+    s1 = F.avg_pool1d(best[None, None, :m], pk, stride=1, padding=pk // 2)
+    s2 = F.max_pool1d(s1, nn, stride=1, padding=nn // 2)[0, 0]
+    np.testing.assert_allclose(res["pooled"], s2.numpy(), rtol=1e-12)
+    order = torch.sort(s2, descending=True, stable=True).indices[:cm]
+    assert res["sel"].tolist() == sorted(order.tolist())
+    assert res["idx"].tolist() == sorted(order.tolist()) + list(range(m, n))
+    np.testing.assert_array_equal(res["ids"], ids.numpy()[res["idx"]])
+    # layers below l_skip must not matter
+    q2 = q.copy()
+    q2[0] *= 3.0
+    np.testing.assert_array_equal(orc.specpc_compress_prompt(q2, k, ids.numpy(), nw, pk, nn, cm, l_skip,
+                                                             w.sm_scale)["idx"], res["idx"])
+    assert orc.specpc_window_weights(4, 6).tolist() == [0.25, 0.5, 0.75, 1.0, 1.0, 1.0]
