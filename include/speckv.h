@@ -171,6 +171,21 @@ speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_
                                    int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
                                    void *workspace, size_t workspace_bytes, void *stream);
 
+/* Prompt compression as printed in Sec. 4.2 / Alg. 2.  Needs n_seqs == 1.  q holds the draft
+ * model's queries of the n_window last prompt rows followed by the lookahead rows, k its prompt
+ * keys, for every layer.  Layers below l_skip are ignored; window row j (1-based) is weighted
+ * j / n_window; the weighted attention probabilities are max-reduced over layers, heads and
+ * rows into one score per prompt token; AvgPool1D(p->pool_k) then MaxPool1D(n_neighbor) over
+ * the non-window tokens (both kernels odd; zero padding for the mean, clipping for the max);
+ * the c_max best tokens (p->c_max) and the window are emitted ascending into idx_out
+ * (capacity min(c_max, m) + n_window) with ids_out[r] = token_ids[idx_out[r]] and *count_out
+ * their number.  p->reduce_op / pool_op are ignored. */
+size_t specpc_compress_workspace_bytes(const speckv_params *p, int32_t l_skip);
+speckv_status specpc_compress_prompt(const speckv_params *p, int32_t l_skip, int32_t n_neighbor,
+                                     const void *q, const void *k, const int32_t *token_ids,
+                                     int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

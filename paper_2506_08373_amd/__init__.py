@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     n_keep,
+    specpc_compress_prompt,
+    specpc_compress_workspace_bytes,
     specpc_select_tokens,
     specpc_workspace_bytes,
     speckv_compact,

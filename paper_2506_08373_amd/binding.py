@@ -45,7 +45,8 @@ class _CParams(ctypes.Structure):
 EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv_workspace_bytes",
            "speckv_score", "speckv_select", "speckv_compact", "speckv_compress",
            "speckv_compress_events",
-           "specpc_workspace_bytes", "specpc_select_tokens")
+           "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
+           "specpc_compress_prompt")
 
 
 def library_path() -> str:
@@ -86,6 +87,11 @@ def load_library() -> ctypes.CDLL:
     lib.specpc_select_tokens.restype = ctypes.c_int
     lib.specpc_select_tokens.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
                                          i32p, vp, ctypes.c_size_t, vp]
+    lib.specpc_compress_workspace_bytes.restype = ctypes.c_size_t
+    lib.specpc_compress_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    lib.specpc_compress_prompt.restype = ctypes.c_int
+    lib.specpc_compress_prompt.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
+                                           i32p, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -230,3 +236,16 @@ def specpc_select_tokens(p: SpecKVParams, top_k: int, n_neighbor: int, q, k, tok
         p.ref(), top_k, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
         _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
         _ptr(count_out, torch.int32), wp, wb, _stream()), "specpc_select_tokens")
+
+
+def specpc_compress_workspace_bytes(p: SpecKVParams, l_skip: int) -> int:
+    return int(load_library().specpc_compress_workspace_bytes(p.ref(), l_skip))
+
+
+def specpc_compress_prompt(p: SpecKVParams, l_skip: int, n_neighbor: int, q, k, token_ids, idx_out,
+                           ids_out, count_out, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().specpc_compress_prompt(
+        p.ref(), l_skip, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+        _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
+        _ptr(count_out, torch.int32), wp, wb, _stream()), "specpc_compress_prompt")

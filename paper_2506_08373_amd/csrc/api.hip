@@ -115,6 +115,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   pl->off_lse = take((size_t)d.L * d.Hkv * d.S * g.RS * g.RSB * sizeof(float));
   pl->off_planes = take((size_t)g.RS * d.L * d.Hkv * d.T * sizeof(float));
   pl->off_pooled = take(one_row_per_call ? (size_t)d.T * sizeof(float) : (size_t)d.L * d.Hkv * d.T * sizeof(float));
+  pl->off_pooled2 = take(one_row_per_call ? (size_t)d.T * sizeof(float) : 0);
   pl->off_sel = take(one_row_per_call ? (size_t)(top_k > 0 ? top_k : 0) * sizeof(int32_t) : 0);
   pl->total = off;
   return SPECKV_OK;
@@ -279,6 +280,64 @@ speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_
   if ((e = launch_select_row(pooled, m, count, sel, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   return from_hip(launch_expand(sel, count, n_in, pl.d.w, n_neighbor, token_ids, idx_out, ids_out,
                                 count_out, hs));
+}
+
+// Parameters of the layers that take part: the first l_skip layers are dropped by moving the base
+// pointers, and the reduction becomes a max over rows, heads and layers with weighted window rows.
+static speckv_status alg2_plan(const speckv_params *p, int32_t l_skip, Plan *pl, speckv_params *eff) {
+  if (p == nullptr || l_skip < 0) return SPECKV_ERR_INVALID_ARG;
+  if (l_skip >= p->n_layers) return SPECKV_ERR_INVALID_ARG;
+  *eff = *p;
+  eff->n_layers = p->n_layers - l_skip;
+  eff->reduce_op = SPECKV_REDUCE_MAX;
+  eff->pool_op = SPECKV_POOL_AVG;
+  const int32_t m_cap = p->c_max < 0 ? 0 : p->c_max;
+  speckv_status st = build_plan(eff, pl, true, m_cap);
+  if (st != SPECKV_OK) return st;
+  pl->d.head_max = 1;
+  pl->d.weight_rows = 1;
+  return SPECKV_OK;
+}
+
+size_t specpc_compress_workspace_bytes(const speckv_params *p, int32_t l_skip) {
+  Plan pl;
+  speckv_params eff;
+  if (alg2_plan(p, l_skip, &pl, &eff) != SPECKV_OK) return 0;
+  return pl.total;
+}
+
+speckv_status specpc_compress_prompt(const speckv_params *p, int32_t l_skip, int32_t n_neighbor,
+                                     const void *q, const void *k, const int32_t *token_ids,
+                                     int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                     void *workspace, size_t workspace_bytes, void *stream) {
+  Plan pl;
+  speckv_params eff;
+  speckv_status st = alg2_plan(p, l_skip, &pl, &eff);
+  if (st != SPECKV_OK) return st;
+  if (n_neighbor < 1 || n_neighbor % 2 == 0) return SPECKV_ERR_INVALID_ARG;
+  if (n_neighbor > SPECKV_MAX_POOL_K) return SPECKV_ERR_UNSUPPORTED;
+  if (q == nullptr || k == nullptr || token_ids == nullptr || idx_out == nullptr || ids_out == nullptr ||
+      count_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k)) return SPECKV_ERR_INVALID_ARG;
+  if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
+  char *ws = static_cast<char *>(workspace);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const Dims &d = pl.d;
+  const char *q0 = static_cast<const char *>(q) + (int64_t)l_skip * d.q_sl * d.elt;
+  const char *k0 = static_cast<const char *>(k) + (int64_t)l_skip * d.kv_sl * d.elt;
+  const int n_in = (int)d.T, m = n_in - d.w;
+  const int count = d.c_max < m ? d.c_max : m;
+  float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
+  float *smooth = reinterpret_cast<float *>(ws + pl.off_pooled);
+  float *spread = reinterpret_cast<float *>(ws + pl.off_pooled2);
+  int32_t *sel = reinterpret_cast<int32_t *>(ws + pl.off_sel);
+  hipError_t e = launch_score(pl, q0, k0, reinterpret_cast<float2 *>(ws + pl.off_part),
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+  if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_reduce_pool_all(pl, planes, nullptr, smooth, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_pool_row(smooth, spread, n_in, d.w, n_neighbor, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_select_row(spread, m, count, sel, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return from_hip(launch_expand(sel, count, n_in, d.w, 0, token_ids, idx_out, ids_out, count_out, hs));
 }
 
 }  // extern "C"

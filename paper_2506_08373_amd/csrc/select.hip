@@ -315,6 +315,16 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
   return hipGetLastError();
 }
 
+hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_window, int32_t pool_k,
+                           hipStream_t st) {
+  const int tiles = (n_in + kPoolTile - 1) / kPoolTile;
+  PlaneMerge pm;
+  pm.n_inner = 1; pm.n_outer = 1; pm.inner_max = 0; pm.outer_max = 0; pm.plane_stride = n_in;
+  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kPoolThreads), 0, st, n_in, n_window,
+                     pool_k, 0, pm, in, (float *)nullptr, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st) {
   const Dims &d = pl.d;
   const int64_t blocks = (int64_t)d.L * d.S * d.Hkv;

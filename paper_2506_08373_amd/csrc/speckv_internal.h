@@ -53,7 +53,7 @@ struct Plan {
   SeqTab t;
   ScoreGeom g;
   // workspace carve-up (byte offsets, 256-aligned)
-  size_t off_part, off_lse, off_planes, off_pooled, off_sel, total;
+  size_t off_part, off_lse, off_planes, off_pooled, off_pooled2, off_sel, total;
 };
 
 inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -85,6 +85,9 @@ hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, f
 // single output row summing every plane of a one-sequence call (prompt-token selection)
 hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *raw, float *pooled,
                                   hipStream_t st);
+// max-pool (kernel pool_k, clipped to [0, n_in - n_window)) of one row of n_in scores
+hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_window, int32_t pool_k,
+                           hipStream_t st);
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st);
 hipError_t launch_select_row(const float *pooled_row, int32_t m, int32_t count, int32_t *sel,
                              hipStream_t st);

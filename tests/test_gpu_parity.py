@@ -386,3 +386,32 @@ def test_specpc_select_tokens(S, n_in, top_k, nb):
     lo = orc.expand_neighbors(sure, n_in, w.n_window, nb)
     hi = orc.expand_neighbors(maybe, n_in, w.n_window, nb)
     assert np.isin(lo, got_idx).all() and np.isin(got_idx, hi).all()
+
+
+@pytest.mark.parametrize("n_in,n_layers,l_skip,n_lookahead,pool_k,n_neighbor,c_max", [
+    (3000, 4, 1, 1, 7, 9, 300),
+    (900, 3, 0, 3, 63, 31, 5000),       # budget above m, wide pools
+    (1500, 10, 8, 1, 1, 1, 100),        # the paper's l_skip; pools of one
+])
+def test_specpc_compress_prompt_alg2(S, n_in, n_layers, l_skip, n_lookahead, pool_k, n_neighbor, c_max):
+    base = workloads.specpc_draft(n_in=n_in, n_layers=n_layers, name="c5_alg2")
+    w = workloads.SpecKVWorkload(**{**base.__dict__, "n_lookahead": n_lookahead, "pool_k": pool_k,
+                                    "c_max": c_max})
+    t = workloads.generate(w)
+    ids = workloads.generate_token_ids(w)
+    ref = orc.specpc_compress_prompt(workloads.to_float64(t["q"][:, 0]), workloads.to_float64(t["k"]),
+                                     ids.numpy(), w.n_window, pool_k, n_neighbor, c_max, l_skip, w.sm_scale)
+    p = make_params(S, w)
+    ws = torch.empty(S.specpc_compress_workspace_bytes(p, l_skip), dtype=torch.uint8, device="cuda")
+    m = n_in - w.n_window
+    cap = min(c_max, m) + w.n_window
+    idx_out = torch.full((cap + 3,), -1, dtype=torch.int32, device="cuda")
+    ids_out = torch.full((cap + 3,), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    S.specpc_compress_prompt(p, l_skip, n_neighbor, t["q"].cuda(), t["k"].cuda(), ids.cuda(), idx_out,
+                             ids_out, count, ws)
+    torch.cuda.synchronize()
+    assert int(count.item()) == cap and (idx_out.cpu().numpy()[cap:] == -1).all()
+    got = idx_out.cpu().numpy()[:cap].astype(np.int64)
+    np.testing.assert_array_equal(ids_out.cpu().numpy()[:cap], ids.numpy()[got])
+    assert_indices_valid(got, ref["pooled"], n_in, w.n_window, c_max, "alg2")
