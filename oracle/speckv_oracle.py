@@ -66,12 +66,32 @@ def observation_positions(n_in: int, n_window: int, n_lookahead: int) -> np.ndar
     return np.concatenate([m + np.arange(n_window), n_in + np.arange(n_lookahead)]).astype(np.int64)
 
 
+def row_lse(q_rows: np.ndarray, k_head: np.ndarray, pos: np.ndarray, sm_scale: float) -> np.ndarray:
+    """Natural-log normaliser of every row: log sum over visible keys of exp(sm_scale * q.k)."""
+    q_rows = np.asarray(q_rows, dtype=np.float64)
+    k_head = np.asarray(k_head, dtype=np.float64)
+    logits = sm_scale * (q_rows @ k_head.T)
+    visible = np.arange(k_head.shape[0])[None, :] <= np.asarray(pos)[:, None]
+    logits = np.where(visible, logits, -np.inf)
+    top = logits.max(axis=1)
+    return top + np.log(np.exp(logits - top[:, None]).sum(axis=1))
+
+
 def attention_probs(q_rows: np.ndarray, k_head: np.ndarray, pos: np.ndarray,
-                    sm_scale: float) -> np.ndarray:
+                    sm_scale: float, lse: Optional[np.ndarray] = None) -> np.ndarray:
     """Row softmax of sm_scale * q k^T over the causally visible prompt keys.
 
     q_rows [R, d], k_head [n, d], pos [R] -> P [R, n]; P[i, j] = 0 for j > pos[i].
+    With `lse` [R] the rows are normalised by exp(lse) supplied by the caller (for example the
+    log-sum-exp of the real forward pass, which also counts the draft keys) instead of by
+    their own sum over the prompt keys.
     """
+    if lse is not None:
+        q_rows = np.asarray(q_rows, dtype=np.float64)
+        k_head = np.asarray(k_head, dtype=np.float64)
+        logits = sm_scale * (q_rows @ k_head.T)
+        visible = np.arange(k_head.shape[0])[None, :] <= np.asarray(pos)[:, None]
+        return np.where(visible, np.exp(logits - np.asarray(lse, dtype=np.float64)[:, None]), 0.0)
     q_rows = np.asarray(q_rows, dtype=np.float64)
     k_head = np.asarray(k_head, dtype=np.float64)
     n = k_head.shape[0]
@@ -85,12 +105,13 @@ def attention_probs(q_rows: np.ndarray, k_head: np.ndarray, pos: np.ndarray,
 
 def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float,
                reduce: str = "sum", row_weights: Optional[np.ndarray] = None,
-               head_reduce: str = "sum") -> np.ndarray:
+               head_reduce: str = "sum", lse_in: Optional[np.ndarray] = None) -> np.ndarray:
     """Importance of every prompt key for every KV head, before pooling.
 
     q [R, Hq, d] (window rows first), k [n, Hkv, d] -> raw [Hkv, n].  Per query head h the
     probabilities P_h[i, j] (optionally scaled by row_weights[i]) are reduced over the rows i
     with `reduce` ("sum" or "max"); the G heads of a group are combined with `head_reduce`.
+    `lse_in` [R, Hq], when given, replaces the rows' own normalisers (see attention_probs).
     """
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -105,7 +126,8 @@ def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float,
     raw = np.zeros((Hkv, n), dtype=np.float64)
     for g in range(Hkv):
         for h in range(g * G, (g + 1) * G):
-            P = attention_probs(q[:, h, :], k[:, g, :], pos, sm_scale)
+            P = attention_probs(q[:, h, :], k[:, g, :], pos, sm_scale,
+                                None if lse_in is None else np.asarray(lse_in)[:, h])
             if row_weights is not None:
                 P = P * np.asarray(row_weights, dtype=np.float64)[:, None]
             per_head = P.sum(axis=0) if reduce == "sum" else P.max(axis=0)
@@ -191,12 +213,12 @@ def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 def speckv_layer(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window: int,
                  pool_k: int, c_max: int, sm_scale: float, reduce: str = "sum",
-                 pool: str = "max") -> Dict[str, np.ndarray]:
+                 pool: str = "max", lse_in: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """One (sequence, layer): scores -> pooled -> indices -> compacted K/V."""
     n = k.shape[0]
     if n < n_window:
         raise ValueError("n_in must be at least n_window")
-    raw = raw_scores(q, k, n_window, sm_scale, reduce=reduce)
+    raw = raw_scores(q, k, n_window, sm_scale, reduce=reduce, lse_in=lse_in)
     pooled = pooled_scores(raw, n_window, pool_k, pool=pool)
     idx = np.stack([keep_indices(pooled[g], n, n_window, c_max) for g in range(k.shape[1])])
     out = {"raw": raw, "pooled": pooled, "idx": idx, "k_out": compact(k, idx)}

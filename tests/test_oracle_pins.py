@@ -480,3 +480,25 @@ def test_specpc_alg2_matches_library_composition():
     np.testing.assert_array_equal(orc.specpc_compress_prompt(q2, k, ids.numpy(), nw, pk, nn, cm, l_skip,
                                                              w.sm_scale)["idx"], res["idx"])
     assert orc.specpc_window_weights(4, 6).tolist() == [0.25, 0.5, 0.75, 1.0, 1.0, 1.0]
+
+
+# ------------------------------------------------------------------ caller-supplied normalisers
+def test_supplied_lse_reduces_to_the_default_and_scales():
+    rng = np.random.default_rng(51)
+    w, a, G, Hkv, d, n = 3, 2, 2, 2, 4, 21
+    q, k, _ = _rand_case(rng, w + a, w, G * Hkv, Hkv, d, n, scale=1.2)
+    pos = orc.observation_positions(n, w, a)
+    lse = np.stack([orc.row_lse(q[:, h], k[:, h // G], pos, 0.6) for h in range(G * Hkv)], axis=1)   # [R, Hq]
+    # independent check of row_lse against the library
+    for h in range(G * Hkv):
+        logits = torch.from_numpy(0.6 * q[:, h] @ k[:, h // G].T)
+        for i in range(w + a):
+            logits[i, pos[i] + 1:] = float("-inf")
+        np.testing.assert_allclose(lse[:, h], torch.logsumexp(logits, dim=1).numpy(), rtol=1e-13)
+    base = orc.raw_scores(q, k, w, 0.6)
+    np.testing.assert_allclose(orc.raw_scores(q, k, w, 0.6, lse_in=lse), base, rtol=1e-12)
+    # a normaliser larger by ln 2 (half the mass elsewhere) halves every score
+    np.testing.assert_allclose(orc.raw_scores(q, k, w, 0.6, lse_in=lse + math.log(2.0)), base / 2, rtol=1e-12)
+    # masked entries stay zero with a supplied normaliser
+    P = orc.attention_probs(q[:, 0], k[:, 0], pos, 0.6, lse[:, 0])
+    assert P[0, n - 1] == 0.0 and P[w, n - 1] > 0.0
