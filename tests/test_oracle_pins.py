@@ -326,10 +326,10 @@ def test_pins_catch_planted_mistakes(monkeypatch):
 
     real_probs = orc.attention_probs
     monkeypatch.setattr(orc, "attention_probs",                                      # scale dropped
-                        lambda q_, k_, pos, sm: real_probs(q_, k_, pos, 1.0))
+                        lambda q_, k_, pos, sm, lse=None: real_probs(q_, k_, pos, 1.0, lse))
     assert closed_form_ok() and not brute_force_ok()
     monkeypatch.setattr(orc, "attention_probs",                                      # keys reversed
-                        lambda q_, k_, pos, sm: real_probs(q_, k_[::-1], pos, sm))
+                        lambda q_, k_, pos, sm, lse=None: real_probs(q_, k_[::-1], pos, sm, lse))
     assert not brute_force_ok()
     monkeypatch.setattr(orc, "attention_probs", real_probs)
 
