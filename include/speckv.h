@@ -126,6 +126,17 @@ speckv_status speckv_score(const speckv_params *p, const void *q, const void *k,
                            float *pooled, float *raw, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* speckv_score with row normalisers supplied by the caller: ONE sweep over K instead of two.
+ * lse_in (fp32, contiguous [L][S][R][n_q_heads]) is the natural-log sum over keys of
+ * exp(sm_scale*q.k) per observation row, for example the log-sum-exp the prefill attention
+ * kernel already produced for these rows (that one also counts the draft keys a lookahead row
+ * attends to, so the probabilities are those of the real forward pass rather than renormalised
+ * over the prompt: Alg. 1's attention matrix A taken from the forward pass).  With lse_in equal
+ * to the row log-sum-exp over the visible prompt keys the result equals speckv_score's. */
+speckv_status speckv_score_lse(const speckv_params *p, const void *q, const void *k,
+                               const float *lse_in, float *pooled, float *raw, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
 /* Selection (Alg. 1 "Select KVs"; Fig. 2: window always retained).  For every (layer,
  * sequence, KV head) writes the min(c_max, m) candidates with the largest pooled score
  * (equal scores: smaller index first), in ascending order, followed by m..n_in-1.
@@ -144,6 +155,11 @@ speckv_status speckv_compact(const speckv_params *p, const void *k, const void *
 speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k,
                               const void *v, int32_t *idx, void *k_out, void *v_out,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* speckv_compress with caller-supplied row normalisers (see speckv_score_lse). */
+speckv_status speckv_compress_lse(const speckv_params *p, const void *q, const void *k,
+                                  const void *v, const float *lse_in, int32_t *idx, void *k_out,
+                                  void *v_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* speckv_compress with per-stage timing marks, for benchmarks and profilers.  `events` is a
  * HOST array of SPECKV_N_STAGE_EVENTS hipEvent_t handles created by the caller; the call

@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     speckv_compact,
     speckv_compress,
     speckv_compress_events,
+    speckv_compress_lse,
+    speckv_score_lse,
     N_STAGE_EVENTS,
     STAGE_NAMES,
     speckv_score,

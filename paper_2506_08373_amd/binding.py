@@ -44,7 +44,7 @@ class _CParams(ctypes.Structure):
 
 EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv_workspace_bytes",
            "speckv_score", "speckv_select", "speckv_compact", "speckv_compress",
-           "speckv_compress_events",
+           "speckv_compress_events", "speckv_score_lse", "speckv_compress_lse",
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
            "specpc_compress_prompt")
 
@@ -75,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.specpc_workspace_bytes.argtypes = [P, ctypes.c_int32]
     lib.speckv_score.restype = ctypes.c_int
     lib.speckv_score.argtypes = [P, vp, vp, f32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_score_lse.restype = ctypes.c_int
+    lib.speckv_score_lse.argtypes = [P, vp, vp, f32p, f32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_compress_lse.restype = ctypes.c_int
+    lib.speckv_compress_lse.argtypes = [P, vp, vp, vp, f32p, i32p, vp, vp, vp, ctypes.c_size_t, vp]
     lib.speckv_select.restype = ctypes.c_int
     lib.speckv_select.argtypes = [P, f32p, i32p, vp, ctypes.c_size_t, vp]
     lib.speckv_compact.restype = ctypes.c_int
@@ -194,6 +198,22 @@ def speckv_score(p: SpecKVParams, q, k, pooled, raw, workspace) -> None:
     _check(load_library().speckv_score(p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
                                        _ptr(pooled, torch.float32), _ptr(raw, torch.float32),
                                        wp, wb, _stream()), "speckv_score")
+
+
+def speckv_score_lse(p: SpecKVParams, q, k, lse_in, pooled, raw, workspace) -> None:
+    """lse_in: fp32 [L, S, R, Hq] natural-log row normalisers."""
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_score_lse(p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+                                           _ptr(lse_in, torch.float32), _ptr(pooled, torch.float32),
+                                           _ptr(raw, torch.float32), wp, wb, _stream()), "speckv_score_lse")
+
+
+def speckv_compress_lse(p: SpecKVParams, q, k, v, lse_in, idx, k_out, v_out, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_compress_lse(
+        p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype), _ptr(v, p.torch_dtype),
+        _ptr(lse_in, torch.float32), _ptr(idx, torch.int32), _ptr(k_out, p.torch_dtype),
+        _ptr(v_out, p.torch_dtype), wp, wb, _stream()), "speckv_compress_lse")
 
 
 def speckv_select(p: SpecKVParams, pooled, idx, workspace=None) -> None:

@@ -170,22 +170,34 @@ size_t specpc_workspace_bytes(const speckv_params *p, int32_t top_k) {
   return pl.total;
 }
 
-speckv_status speckv_score(const speckv_params *p, const void *q, const void *k, float *pooled,
-                           float *raw, void *workspace, size_t workspace_bytes, void *stream) {
+static speckv_status score_impl(const speckv_params *p, const void *q, const void *k, const float *lse_in,
+                                bool want_lse, float *pooled, float *raw, void *workspace,
+                                size_t workspace_bytes, void *stream) {
   Plan pl;
   speckv_status st = build_plan(p, &pl, false, 0);
   if (st != SPECKV_OK) return st;
-  if (q == nullptr || k == nullptr || pooled == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if (q == nullptr || k == nullptr || pooled == nullptr || (want_lse && lse_in == nullptr)) return SPECKV_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || (reinterpret_cast<uintptr_t>(pooled) & 3u) ||
-      (reinterpret_cast<uintptr_t>(raw) & 3u)) return SPECKV_ERR_INVALID_ARG;
+      (reinterpret_cast<uintptr_t>(raw) & 3u) || (reinterpret_cast<uintptr_t>(lse_in) & 3u)) return SPECKV_ERR_INVALID_ARG;
   if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
   char *ws = static_cast<char *>(workspace);
   hipStream_t hs = static_cast<hipStream_t>(stream);
   float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
   hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
-                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, nullptr, lse_in);
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
   return from_hip(launch_reduce_pool(pl, planes, raw, pooled, hs));
+}
+
+speckv_status speckv_score(const speckv_params *p, const void *q, const void *k, float *pooled,
+                           float *raw, void *workspace, size_t workspace_bytes, void *stream) {
+  return score_impl(p, q, k, nullptr, false, pooled, raw, workspace, workspace_bytes, stream);
+}
+
+speckv_status speckv_score_lse(const speckv_params *p, const void *q, const void *k, const float *lse_in,
+                               float *pooled, float *raw, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+  return score_impl(p, q, k, lse_in, true, pooled, raw, workspace, workspace_bytes, stream);
 }
 
 speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
@@ -213,7 +225,8 @@ speckv_status speckv_compact(const speckv_params *p, const void *k, const void *
 
 static speckv_status compress_impl(const speckv_params *p, const void *q, const void *k, const void *v,
                                    int32_t *idx, void *k_out, void *v_out, void *workspace,
-                                   size_t workspace_bytes, void *stream, hipEvent_t *ev) {
+                                   size_t workspace_bytes, void *stream, hipEvent_t *ev,
+                                   const float *lse_in = nullptr) {
   Plan pl;
   speckv_status st = build_plan(p, &pl, false, 0);
   if (st != SPECKV_OK) return st;
@@ -227,7 +240,7 @@ static speckv_status compress_impl(const speckv_params *p, const void *q, const 
   float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
   float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
   hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
-                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev);
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev, lse_in);
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
@@ -242,6 +255,13 @@ speckv_status speckv_compress(const speckv_params *p, const void *q, const void 
                               int32_t *idx, void *k_out, void *v_out, void *workspace,
                               size_t workspace_bytes, void *stream) {
   return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+speckv_status speckv_compress_lse(const speckv_params *p, const void *q, const void *k, const void *v,
+                                  const float *lse_in, int32_t *idx, void *k_out, void *v_out,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  if (lse_in == nullptr || (reinterpret_cast<uintptr_t>(lse_in) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream, nullptr, lse_in);
 }
 
 speckv_status speckv_compress_events(const speckv_params *p, const void *q, const void *k, const void *v,

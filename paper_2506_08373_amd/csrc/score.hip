@@ -55,6 +55,7 @@ struct ScoreArgs {
   const char *k;
   float2 *part;     // [unit][chunk][RSB] (max2, sum) per row, unit = (layer, head, row super-block)
   float *lse;       // [layer][head][seq][RS*RSB]
+  const float *lse_in;   // optional caller-supplied natural-log normalisers [L][S][R][Hq]
   float *planes;    // [RS][layer][Hkv*T]
 };
 
@@ -455,6 +456,25 @@ __global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(
   }
 }
 
+// Converts caller-supplied natural-log normalisers [L][S][R][Hq] into the padded log2 layout
+// the column-reduction sweep reads.
+__global__ __launch_bounds__(256) void lse_import_kernel(ScoreArgs A) {
+  const Dims &d = A.d;
+  const int RSB = A.g.RSB;
+  const int unit = blockIdx.x;            // (layer, head, row super-block)
+  const int s = blockIdx.y;
+  const int rs = unit % A.g.RS;
+  const int lh = unit / A.g.RS;           // layer * Hkv + head
+  const int g = lh % d.Hkv, layer = lh / d.Hkv;
+  for (int lr = threadIdx.x; lr < RSB; lr += blockDim.x) {
+    int hh, i;
+    float v = 0.f;
+    if (decode_row(d, A.g, rs, lr, &hh, &i))
+      v = A.lse_in[(((int64_t)layer * d.S + s) * d.R + i) * d.Hq + g * d.G + hh] * 1.4426950408889634f;
+    A.lse[((int64_t)lh * d.S + s) * ((int64_t)A.g.RS * RSB) + rs * RSB + lr] = v;
+  }
+}
+
 template <typename K>
 hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -481,10 +501,14 @@ hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   const size_t lds = score_lds_bytes<ELT, D, MB, NW>();
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-  if ((e = launch_sweep<ELT, D, MB, NW, 1, 0>(A, lds, st)) != hipSuccess) return e;
+  if (A.lse_in == nullptr && (e = launch_sweep<ELT, D, MB, NW, 1, 0>(A, lds, st)) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
-  hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS * (A.g.RSB / kMergeRows), A.d.S),
-                     dim3(kMergeRows * kMergeSlices), 0, st, A);
+  if (A.lse_in == nullptr) {
+    hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS * (A.g.RSB / kMergeRows), A.d.S),
+                       dim3(kMergeRows * kMergeSlices), 0, st, A);
+  } else {
+    hipLaunchKernelGGL(lse_import_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS, A.d.S), dim3(256), 0, st, A);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
   e = A.d.reduce_max ? launch_sweep<ELT, D, MB, NW, 2, 1>(A, lds, st) : launch_sweep<ELT, D, MB, NW, 2, 0>(A, lds, st);
@@ -513,11 +537,11 @@ hipError_t dispatch_geom(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
 }  // namespace
 
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
-                        float *planes, hipStream_t st, hipEvent_t *events) {
+                        float *planes, hipStream_t st, hipEvent_t *events, const float *lse_in) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
-  A.part = part; A.lse = lse; A.planes = planes;
+  A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in;
   if (pl.d.elt == 2) {
     return pl.d.D == 128 ? dispatch_geom<2, 128>(A, st, events) : dispatch_geom<2, 64>(A, st, events);
   }

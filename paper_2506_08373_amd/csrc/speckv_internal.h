@@ -63,8 +63,11 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const in
                           void *k_out, void *v_out, hipStream_t st);
 // `events`, when not null, holds 4 hipEvent_t recorded before pass 1, before the merge of the
 // row statistics, before pass 2 and after pass 2.
+// `lse_in`, when not null, holds natural-log row normalisers [L][S][R][Hq]; the row-statistics
+// sweep is skipped and only the column reduction runs.
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
-                        float *planes, hipStream_t st, hipEvent_t *events = nullptr);
+                        float *planes, hipStream_t st, hipEvent_t *events = nullptr,
+                        const float *lse_in = nullptr);
 // Row `lr` of super-block `rs` -> (head in group, observation row); false for padding rows.
 // Heads never share a 32-row block: each head's R rows are padded to Rp, and a super-block holds
 // either HPS whole heads or one of the PPH slices of a single head.

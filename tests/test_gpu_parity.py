@@ -415,3 +415,51 @@ def test_specpc_compress_prompt_alg2(S, n_in, n_layers, l_skip, n_lookahead, poo
     got = idx_out.cpu().numpy()[:cap].astype(np.int64)
     np.testing.assert_array_equal(ids_out.cpu().numpy()[:cap], ids.numpy()[got])
     assert_indices_valid(got, ref["pooled"], n_in, w.n_window, c_max, "alg2")
+
+
+@pytest.mark.parametrize("shift", [0.0, 0.37])
+def test_scores_with_supplied_row_normalisers(S, shift):
+    """One sweep with caller-supplied log-sum-exps: equals the two-sweep path when they are the
+    rows' own normalisers, and the oracle with any other value."""
+    w = workloads.ragged_batch(n_layers=2, lo=300, hi=1800, n_seqs=2, seed=11, name="c4_lse")
+    t = workloads.generate(w)
+    q64, k64 = workloads.to_float64(t["q"]), workloads.to_float64(t["k"])
+    cu, G = w.cu_seqlens, w.group
+    L, Sn, R, Hq = w.n_layers, w.n_seqs, w.n_rows, w.n_q_heads
+    lse = np.zeros((L, Sn, R, Hq))
+    for layer in range(L):
+        for s in range(Sn):
+            pos = orc.observation_positions(w.seq_lens[s], w.n_window, w.n_lookahead)
+            for h in range(Hq):
+                lse[layer, s, :, h] = orc.row_lse(q64[layer, s, :, h], k64[layer, cu[s]:cu[s + 1], h // G],
+                                                  pos, w.sm_scale) + shift * (1 + h % 3)
+    p = make_params(S, w)
+    H, T = w.n_kv_heads, w.total_tokens
+    pooled = torch.empty((L, H * T), dtype=torch.float32, device="cuda")
+    raw = torch.empty_like(pooled)
+    ws = alloc_ws(S, p)
+    S.speckv_score_lse(p, t["q"].cuda(), t["k"].cuda(), torch.from_numpy(lse).float().cuda(), pooled, raw, ws)
+    torch.cuda.synchronize()
+    raw_h = raw.cpu().numpy()
+    lse32 = lse.astype(np.float32).astype(np.float64)              # the library sees the fp32 rounding
+    for layer in range(L):
+        for s in range(Sn):
+            want = orc.raw_scores(q64[layer, s], k64[layer, cu[s]:cu[s + 1]], w.n_window, w.sm_scale,
+                                  lse_in=lse32[layer, s])
+            assert_scores_close(split_scores(w, raw_h, layer, s), want, "raw with lse l%d s%d" % (layer, s))
+    if shift == 0.0:
+        pooled2 = torch.empty_like(pooled)
+        S.speckv_score(p, t["q"].cuda(), t["k"].cuda(), pooled2, None, ws)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(pooled.cpu().numpy(), pooled2.cpu().numpy(), rtol=1e-4, atol=1e-9)
+    # fused variant runs and selects from the same scores
+    KT = S.total_keep(p)
+    idx = torch.empty((L, H * KT), dtype=torch.int32, device="cuda")
+    k_out = torch.empty((L, H * KT, w.head_dim), dtype=w.torch_dtype, device="cuda")
+    v_out = torch.empty_like(k_out)
+    S.speckv_compress_lse(p, t["q"].cuda(), t["k"].cuda(), t["v"].cuda(), torch.from_numpy(lse).float().cuda(),
+                          idx, k_out, v_out, ws)
+    idx2 = torch.empty_like(idx)
+    S.speckv_select(p, pooled, idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
