@@ -72,6 +72,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lse-variant", action="store_true",
+                    help="also time the single-sweep variant with caller-supplied row normalisers")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 "
                          "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
@@ -170,6 +172,35 @@ def main() -> int:
     ms_per_step = elapsed / args.steps * 1e3
     value = w.key_units / (elapsed / args.steps)
 
+    # Context figure (not the headline): the same step when the caller already holds the row
+    # log-sum-exps (e.g. from the prefill attention kernel) and scoring needs one sweep only.
+    lse_variant = None
+    if args.lse_variant:
+        lse_in = torch.empty((L, w.n_seqs, w.n_rows, w.n_q_heads), dtype=torch.float32, device="cuda")
+        cu = w.cu_seqlens
+        for layer in range(L):
+            for s_ in range(w.n_seqs):
+                kk = k[layer, cu[s_]:cu[s_ + 1]].float()                       # [n, Hkv, d]
+                qq = q[layer, s_].float().view(w.n_rows, H, w.group, d)        # [R, Hkv, G, d]
+                logits = torch.einsum("rhgd,nhd->rhgn", qq, kk) * w.sm_scale   # causal mask ignored: timing only
+                lse_in[layer, s_] = torch.logsumexp(logits, dim=-1).reshape(w.n_rows, w.n_q_heads)
+                del logits, kk, qq
+        for _ in range(args.warmup):
+            S.speckv_compress_lse(p, q, k, v, lse_in, idx, k_out, v_out, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            S.speckv_compress_lse(p, q, k, v, lse_in, idx, k_out, v_out, ws)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        lse_variant = {"ms_per_step": round(el / args.steps * 1e3, 4),
+                       "value": round(w.key_units / (el / args.steps), 1), "unit": "keys/s",
+                       "note": "speckv_compress_lse: row normalisers supplied by the caller, one sweep over K"}
+        del lse_in
+        # restore the headline outputs for the parity check below
+        S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
+        torch.cuda.synchronize()
+
     cpu_baseline = None
     parity = None
     if not args.no_cpu_baseline:
@@ -217,6 +248,7 @@ def main() -> int:
         "roofline": roofline,
         "kernels": kernels,
         "k_read_GBps_in_dominant_kernel": round(k_read_gbs, 1),
+        "single_sweep_variant": lse_variant,
         "cpu_baseline": cpu_baseline,
         "parity_check": parity,
         "input_generation_s": round(gen_s, 1),
