@@ -82,8 +82,9 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   else if (m_pad <= 256 || d.D * d.elt > 256) { g.NW = 8; g.MB = 1; }
   else { g.NW = 8; g.MB = 2; }
   g.RSB = g.NW * g.MB * 32;
-  if (g.Rp <= g.RSB) {            // whole heads per super-block
-    g.HPS = g.RSB / g.Rp; g.PPH = 1; g.RS = (d.G + g.HPS - 1) / g.HPS;
+  if (g.Rp <= g.RSB) {            // whole heads per super-block, spread evenly over the super-blocks
+    const int fit = g.RSB / g.Rp;
+    g.PPH = 1; g.RS = (d.G + fit - 1) / fit; g.HPS = (d.G + g.RS - 1) / g.RS;
   } else {                        // one head spread over PPH super-blocks
     g.HPS = 1; g.PPH = (g.Rp + g.RSB - 1) / g.RSB; g.RS = d.G * g.PPH;
   }

@@ -28,6 +28,8 @@
 // is element (8*(i/4) + 4*(l/32) + i%4, l%32).  Both operands take their k-slices from the same
 // 16-byte chunks of the head dimension (half l/32 reads chunks [half*NCS, half*NCS+NCS)), so the
 // contraction is over all d channels whatever order the hardware assigns inside a slice.
+#include <type_traits>
+
 #include "speckv_internal.h"
 
 namespace speckv {
@@ -108,7 +110,7 @@ constexpr size_t score_lds_bytes() {
 //           loop body is straight-line code without any bounds or mask logic;
 //           true: the tail of a sequence (keys that window rows may not see, end of sequence)
 template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
-__global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
+__device__ __forceinline__ void score_body(const ScoreArgs &A) {
   using TL = Tile<ELT, D>;
   constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
   constexpr int RSB = NW * MB * 32;
@@ -144,12 +146,22 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
   const int ntiles = (key_end - key_begin + KT - 1) / KT;
   const float c2 = d.sm_scale * 1.4426950408889634f;
 
+  // 32-row block b of the super-block belongs to wave b % NW (its row block b / NW), so that a
+  // partly filled super-block still spreads its blocks evenly over the SIMDs.  Blocks past the
+  // last valid row are skipped: nact = how many of this wave's MB blocks hold rows.
+  int nblk;
+  if (A.g.PPH == 1) nblk = min(A.g.HPS, d.G - rs * A.g.HPS) * (A.g.Rp / 32);
+  else nblk = (min(RSB, d.R - (rs % A.g.PPH) * RSB) + 31) / 32;
+  const int nact = __builtin_amdgcn_readfirstlane(max(0, min(MB, (nblk - wv + NW - 1) / NW)));
+  if (PASS == 2)   // slots of skipped blocks must read as zero when the tile partials are merged
+    for (int x = tid; x < 2 * NW * MB * KT; x += NW * 64) csum[x] = 0.f;
+
   // ---- Q fragments of this wave's row blocks, resident for the whole sweep
   u32x4 qf[MB][NCS];
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
     int hh, i;
-    const bool valid = decode_row(d, A.g, rs, (wv * MB + rb) * 32 + l32, &hh, &i);
+    const bool valid = decode_row(d, A.g, rs, (rb * NW + wv) * 32 + l32, &hh, &i);
     const char *qp = A.q + ((int64_t)layer * d.q_sl + (int64_t)s * d.q_ss + (int64_t)(valid ? i : 0) * d.q_sr +
                             (int64_t)(g * d.G + (valid ? hh : 0)) * d.q_sh) * ELT + (half * NCS) * 16;
 #pragma unroll
@@ -169,7 +181,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int lr = (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+        const int lr = (rb * NW + wv) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
         int hh, io;
         const bool valid = decode_row(d, A.g, rs, lr, &hh, &io);
         float v = -lp[rs * RSB + lr];                       // the lse buffer covers the padded rows
@@ -251,71 +263,77 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
       // (no back-to-back dependent MFMAs); the fragments of the next block are fetched while
       // the vector pipe turns the scores into probabilities.  The second wave on the SIMD
       // runs its MFMAs underneath that vector work.
-      u32x4 bf[NCS];
-      SPECKV_LOAD_BFRAG(bf, buf, 0)
+      // NACT = number of active row blocks of this wave (compile-time copy of nact)
+      auto fast_tile = [&](auto nact_c) {
+        constexpr int NACT = decltype(nact_c)::value;
+        u32x4 bf[NCS];
+        SPECKV_LOAD_BFRAG(bf, buf, 0)
 #pragma unroll
-      for (int kb = 0; kb < KT / 32; ++kb) {
-        f32x16 acc[MB];
+        for (int kb = 0; kb < KT / 32; ++kb) {
+          f32x16 acc[NACT];
 #pragma unroll
-        for (int rb = 0; rb < MB; ++rb) acc[rb] = (f32x16){0};
+          for (int rb = 0; rb < NACT; ++rb) acc[rb] = (f32x16){0};
 #pragma unroll
-        for (int cs = 0; cs < NCS; ++cs)
+          for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
-          for (int rb = 0; rb < MB; ++rb)
-            acc[rb] = PASS == 1 ? mma_chunk<ELT>(bf[cs], qf[rb][cs], acc[rb]) : mma_chunk<ELT>(qf[rb][cs], bf[cs], acc[rb]);
-        if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
-        if (PASS == 1) {
+            for (int rb = 0; rb < NACT; ++rb)
+              acc[rb] = PASS == 1 ? mma_chunk<ELT>(bf[cs], qf[rb][cs], acc[rb]) : mma_chunk<ELT>(qf[rb][cs], bf[cs], acc[rb]);
+          if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
+          if (PASS == 1) {
 #pragma unroll
-          for (int rb = 0; rb < MB; ++rb) {
-            // branch-free online softmax step for the lane's query row
-            float tmax = fmaxf(fmaxf(acc[rb][0], acc[rb][1]), acc[rb][2]);
+            for (int rb = 0; rb < NACT; ++rb) {
+              // branch-free online softmax step for the lane's query row
+              float tmax = fmaxf(fmaxf(acc[rb][0], acc[rb][1]), acc[rb][2]);
 #pragma unroll
-            for (int i = 3; i < 15; i += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][i]), acc[rb][i + 1]);
-            tmax = fmaxf(tmax, acc[rb][15]);
-            const float mnew = fmaxf(mrun[rb], tmax * c2);
-            const float scale = __builtin_amdgcn_exp2f(mrun[rb] - mnew);
-            const float nm = -mnew;
-            float sum = 0.f;
+              for (int i = 3; i < 15; i += 2) tmax = fmaxf(fmaxf(tmax, acc[rb][i]), acc[rb][i + 1]);
+              tmax = fmaxf(tmax, acc[rb][15]);
+              const float mnew = fmaxf(mrun[rb], tmax * c2);
+              const float scale = __builtin_amdgcn_exp2f(mrun[rb] - mnew);
+              const float nm = -mnew;
+              float sum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nm));
-            lrun[rb] = fmaf(lrun[rb], scale, sum);
-            mrun[rb] = mnew;
-          }
-        } else {
-          // probabilities in batches of 8: all multiply-adds, then all exp2, then the reduction,
-          // so that no instruction waits on the transcendental issued just before it
-          float colsum = 0.f;
+              for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nm));
+              lrun[rb] = fmaf(lrun[rb], scale, sum);
+              mrun[rb] = mnew;
+            }
+          } else {
+            // probabilities in batches of 8: all multiply-adds, then all exp2, then the reduction,
+            // so that no instruction waits on the transcendental issued just before it
+            float colsum = 0.f;
 #pragma unroll
-          for (int rb = 0; rb < MB; ++rb) {
-            if (RED == 1) colsum = 0.f;
+            for (int rb = 0; rb < NACT; ++rb) {
+              if (RED == 1) colsum = 0.f;
 #pragma unroll
-            for (int h8 = 0; h8 < 16; h8 += 8) {
-              float x[8];
+              for (int h8 = 0; h8 < 16; h8 += 8) {
+                float x[8];
 #pragma unroll
-              for (int i = 0; i < 8; ++i) x[i] = fmaf(acc[rb][h8 + i], c2, nlse[rb][h8 + i]);
+                for (int i = 0; i < 8; ++i) x[i] = fmaf(acc[rb][h8 + i], c2, nlse[rb][h8 + i]);
 #pragma unroll
-              for (int i = 0; i < 8; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
-              __builtin_amdgcn_sched_barrier(0);
-              if (RED == 0) {
+                for (int i = 0; i < 8; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (RED == 0) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) colsum += x[i];
-              } else {
+                  for (int i = 0; i < 8; ++i) colsum += x[i];
+                } else {
 #pragma unroll
-                for (int i = 0; i < 8; i += 2) colsum = fmaxf(fmaxf(colsum, x[i]), x[i + 1]);
+                  for (int i = 0; i < 8; i += 2) colsum = fmaxf(fmaxf(colsum, x[i]), x[i + 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
               }
-              __builtin_amdgcn_sched_barrier(0);
+              if (RED == 1) {        // one value per 32-row block: blocks of a head are merged at the flush
+                colsum = max_other_half(colsum);
+                if (half == 0) csum[(size_t)buf * NW * MB * KT + (rb * NW + wv) * KT + kb * 32 + l32] = colsum;
+              }
             }
-            if (RED == 1) {        // one value per 32-row block: blocks of a head are merged at the flush
-              colsum = max_other_half(colsum);
-              if (half == 0) csum[(size_t)buf * NW * MB * KT + (wv * MB + rb) * KT + kb * 32 + l32] = colsum;
+            if (RED == 0) {
+              colsum = add_other_half(colsum);
+              if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
             }
-          }
-          if (RED == 0) {
-            colsum = add_other_half(colsum);
-            if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
           }
         }
-      }
+      };
+      if (nact == MB) fast_tile(std::integral_constant<int, MB>{});
+      else if (MB > 1 && nact == 1) fast_tile(std::integral_constant<int, 1>{});
     } else {
       // Tail tiles: keys above m are hidden from some window rows; keys >= n_s do not exist.
 #pragma unroll 1
@@ -326,12 +344,13 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
         if (PASS == 1) {
 #pragma unroll
           for (int rb = 0; rb < MB; ++rb) {
+            if (rb >= nact) continue;
             f32x16 acc = {0};
 #pragma unroll
             for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
             // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
             int hh_, iobs;
-            decode_row(d, A.g, rs, (wv * MB + rb) * 32 + l32, &hh_, &iobs);
+            decode_row(d, A.g, rs, (rb * NW + wv) * 32 + l32, &hh_, &iobs);
             const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -355,6 +374,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
           const int key = tk0 + kb * 32 + l32;
 #pragma unroll
           for (int rb = 0; rb < MB; ++rb) {
+            if (rb >= nact) continue;
             f32x16 acc = {0};
 #pragma unroll
             for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(qf[rb][cs], bf[cs], acc);
@@ -365,7 +385,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               int hh_, iobs;
-              decode_row(d, A.g, rs, (wv * MB + rb) * 32 + 8 * (i >> 2) + 4 * half + (i & 3), &hh_, &iobs);
+              decode_row(d, A.g, rs, (rb * NW + wv) * 32 + 8 * (i >> 2) + 4 * half + (i & 3), &hh_, &iobs);
               const int last = iobs < d.w ? m + iobs : n_s - 1;
               if (key > last) p[i] = 0.f;
             }
@@ -377,7 +397,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #pragma unroll
               for (int i = 0; i < 16; ++i) cm = fmaxf(cm, p[i]);
               cm = max_other_half(cm);
-              if (half == 0) csum[(size_t)buf * NW * MB * KT + (wv * MB + rb) * KT + kb * 32 + l32] = cm;
+              if (half == 0) csum[(size_t)buf * NW * MB * KT + (rb * NW + wv) * KT + kb * 32 + l32] = cm;
             }
           }
           if (RED == 0) {
@@ -400,7 +420,7 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
       const float mo = __shfl_xor(mrun[rb], 32, 64), lo = __shfl_xor(lrun[rb], 32, 64);
       const float mm = fmaxf(mrun[rb], mo);
       const float ll = lrun[rb] * __builtin_amdgcn_exp2f(mrun[rb] - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
-      if (half == 0) pp[(wv * MB + rb) * 32 + l32] = make_float2(mm, ll);
+      if (half == 0) pp[(rb * NW + wv) * 32 + l32] = make_float2(mm, ll);
     }
   } else if (ntiles > 0) {
     SPECKV_FLUSH_TILE(ntiles - 1)
@@ -410,6 +430,18 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(ScoreArgs A) {
 #undef SPECKV_LOAD_TILE
 #undef SPECKV_LOAD_BFRAG
 #undef SPECKV_FLUSH_TILE
+
+// The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
+// then schedules its online-softmax step more freely); the column sweep does better without.
+template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_kernel_rows(ScoreArgs A) {
+  score_body<ELT, D, MB, NW, PASS, RED, MASKED>(A);
+}
+
+template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+__global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
+  score_body<ELT, D, MB, NW, PASS, RED, MASKED>(A);
+}
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
 // A block covers 64 rows; its 4 waves split the chunks and merge their partial pairs in LDS.
@@ -489,11 +521,12 @@ hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
   const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
   hipError_t e;
   if (A.g.n_fast_chunks > 0) {
-    e = launch_one(score_kernel<ELT, D, MB, NW, PASS, RED, false>, A, dim3(A.g.n_fast_chunks, units),
-                   dim3(NW * 64), lds, st);
+    const dim3 grid(A.g.n_fast_chunks, units), block(NW * 64);
+    if (PASS == 1 && NW == 8) e = launch_one(score_kernel_rows<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    else e = launch_one(score_kernel_cols<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     if (e != hipSuccess) return e;
   }
-  return launch_one(score_kernel<ELT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
+  return launch_one(score_kernel_cols<ELT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
 }
 
 template <int ELT, int D, int MB, int NW>
