@@ -47,6 +47,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   for (int64_t sv : strides)
     if (sv < 0 || (sv * d.elt) % 16 != 0) return SPECKV_ERR_INVALID_ARG;
   if (d.q_sr < d.D || d.q_sh < d.D || d.kv_st < d.D || d.kv_sh < d.D) return SPECKV_ERR_INVALID_ARG;
+  if (d.kv_st * d.elt >= ((int64_t)1 << 23)) return SPECKV_ERR_UNSUPPORTED;   // 32-bit offsets inside a 128-key tile
 
   SeqTab &t = pl->t;
   t.n_seqs = d.S;

@@ -195,17 +195,30 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
   const int64_t tokb = d.kv_st * ELT;
   const int st_row = (lane * 16) / ROWB, st_slot = ((lane * 16) % ROWB) / 16;
+  // unmasked sweep: the lane's byte offset inside a tile never changes, only the (uniform) tile
+  // base moves, so the loads use a scalar base plus a 32-bit lane offset
+  uint32_t loff[SEG_PER_WAVE];
+#pragma unroll
+  for (int it = 0; it < SEG_PER_WAVE; ++it) {
+    const int r_ = (it * NW + wv) * RPS + st_row;
+    loff[it] = (uint32_t)r_ * (uint32_t)tokb + (uint32_t)((st_slot ^ TL::swizzle(r_)) * 16);
+  }
 #define SPECKV_LOAD_TILE(tile_, buf_)                                                         \
   {                                                                                           \
     const int k0_ = key_begin + (tile_) * KT;                                                 \
+    const char *tbase_ = kbase + (int64_t)k0_ * tokb;                                         \
     _Pragma("unroll") for (int it = 0; it < SEG_PER_WAVE; ++it) {                             \
       const int seg_ = it * NW + wv;                                                          \
-      const int r_ = seg_ * RPS + st_row;                                                     \
-      const int c_ = st_slot ^ TL::swizzle(r_);                                               \
-      /* rows past the end of the sequence re-read its last key; they are masked later */     \
-      const int key_ = MASKED ? min(k0_ + r_, n_s - 1) : k0_ + r_;                            \
+      const char *src_;                                                                       \
+      if (MASKED) {                                                                           \
+        const int r_ = seg_ * RPS + st_row;                                                   \
+        /* rows past the end of the sequence re-read its last key; they are masked later */   \
+        src_ = kbase + (int64_t)min(k0_ + r_, n_s - 1) * tokb + (st_slot ^ TL::swizzle(r_)) * 16; \
+      } else {                                                                                \
+        src_ = tbase_ + loff[it];                                                             \
+      }                                                                                       \
       __builtin_amdgcn_global_load_lds(                                                       \
-          (const __attribute__((address_space(1))) void *)(kbase + (int64_t)key_ * tokb + c_ * 16),   \
+          (const __attribute__((address_space(1))) void *)src_,                               \
           (__attribute__((address_space(3))) void *)(kbuf + (buf_) * TILE_BYTES + seg_ * 1024), 16, 0, 0); \
     }                                                                                         \
   }
@@ -253,8 +266,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   }
   __syncthreads();
 
-  for (int tile = 0; tile < ntiles; ++tile) {
-    const int buf = tile & 1;
+  // one tile of the sweep; the LDS buffer index is a compile-time constant so that every LDS
+  // address below is a register plus an immediate
+  auto do_tile = [&](int tile, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
     if (tile + 1 < ntiles) SPECKV_LOAD_TILE(tile + 1, buf ^ 1)
     if (PASS == 2 && tile > 0) SPECKV_FLUSH_TILE(tile - 1)
     const int tk0 = key_begin + tile * KT;
@@ -410,6 +425,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     // the next tile must have landed in LDS, and every wave must be done with this one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+  };
+  for (int tile = 0; tile < ntiles; tile += 2) {
+    do_tile(tile, std::integral_constant<int, 0>{});
+    if (tile + 1 < ntiles) do_tile(tile + 1, std::integral_constant<int, 1>{});
   }
 
   if (PASS == 1) {
