@@ -11,6 +11,7 @@ namespace {
 
 constexpr int64_t kTokenLimit = (int64_t)1 << 30;   // total tokens per call
 constexpr int kTargetWorkgroups = 1024;             // scoring grid: about 4 workgroups per CU
+constexpr int kCUs = 256;                           // compute units of an MI355X
 constexpr int kChunkAlign = 128;                    // chunk = whole LDS key tiles
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -101,8 +102,14 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
     t.tail0[s] = visible_to_all / kt * kt;
     fast_keys += t.tail0[s];
   }
-  const int64_t want_chunks = (kTargetWorkgroups + units - 1) / units;
-  int64_t kc = align_up((fast_keys + want_chunks - 1) / want_chunks, kChunkAlign);
+  // Chunk length: about four workgroups per CU for large problems; small problems get longer
+  // chunks (up to 2048 keys) as long as one workgroup per CU remains, because every workgroup
+  // pays for loading its Q fragments and row normalisers.
+  const int64_t many = (kTargetWorkgroups + units - 1) / units, few = (kCUs + units - 1) / units;
+  int64_t kc = align_up((fast_keys + many - 1) / many, kChunkAlign);
+  int64_t kc_few = align_up((fast_keys + few - 1) / few, kChunkAlign);
+  if (kc_few > 16 * kChunkAlign) kc_few = 16 * kChunkAlign;
+  if (kc < kc_few) kc = kc_few;
   if (kc < 4 * kChunkAlign) kc = 4 * kChunkAlign;
   g.KC = (int32_t)kc;
   t.cc[0] = 0;

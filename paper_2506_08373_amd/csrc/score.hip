@@ -156,12 +156,24 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   if (PASS == 2)   // slots of skipped blocks must read as zero when the tile partials are merged
     for (int x = tid; x < 2 * NW * MB * KT; x += NW * 64) csum[x] = 0.f;
 
+  // head and first observation row of each of this wave's 32-row blocks (a block never mixes
+  // heads, so one division per block replaces one per row)
+  int blk_head[MB], blk_i0[MB];
+#pragma unroll
+  for (int rb = 0; rb < MB; ++rb) {
+    int hh, i0;
+    const bool ok = decode_row(d, A.g, rs, (rb * NW + wv) * 32, &hh, &i0);
+    blk_head[rb] = ok ? hh : -1;       // -1: the whole block is padding
+    blk_i0[rb] = i0;
+  }
+#define SPECKV_ROW_VALID(rb_, r32_) (blk_head[rb_] >= 0 && blk_i0[rb_] + (r32_) < d.R)
+
   // ---- Q fragments of this wave's row blocks, resident for the whole sweep
   u32x4 qf[MB][NCS];
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
-    int hh, i;
-    const bool valid = decode_row(d, A.g, rs, (rb * NW + wv) * 32 + l32, &hh, &i);
+    const bool valid = SPECKV_ROW_VALID(rb, l32);
+    const int hh = blk_head[rb], i = blk_i0[rb] + l32;
     const char *qp = A.q + ((int64_t)layer * d.q_sl + (int64_t)s * d.q_ss + (int64_t)(valid ? i : 0) * d.q_sr +
                             (int64_t)(g * d.G + (valid ? hh : 0)) * d.q_sh) * ELT + (half * NCS) * 16;
 #pragma unroll
@@ -181,13 +193,34 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int lr = (rb * NW + wv) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-        int hh, io;
-        const bool valid = decode_row(d, A.g, rs, lr, &hh, &io);
+        const int r32 = 8 * (i >> 2) + 4 * half + (i & 3);
+        const int lr = (rb * NW + wv) * 32 + r32;
+        const bool valid = SPECKV_ROW_VALID(rb, r32);
+        const int io = blk_i0[rb] + r32;
         float v = -lp[rs * RSB + lr];                       // the lse buffer covers the padded rows
         if (d.weight_rows && io < d.w) v += log2f((float)(io + 1) / (float)d.w);   // row weight folded in
         nlse[rb][i] = valid ? v : -INFINITY;                // padded rows contribute 2^-inf = 0
       }
+  }
+
+  // ---- masked sweep: last key each row may see (window row i sees keys <= m + i, a lookahead
+  // row the whole prompt), computed once instead of per score
+  int last1[MB];                     // pass 1: the lane's own query row per row block
+  int last2[MB][16];                 // pass 2: the 16 rows a lane holds per row block
+  if (MASKED) {
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+      if (PASS == 1) {
+        const int io = blk_i0[rb] + l32;
+        last1[rb] = io < d.w ? m + io : n_s - 1;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int io = blk_i0[rb] + 8 * (i >> 2) + 4 * half + (i & 3);
+          last2[rb][i] = io < d.w ? m + io : n_s - 1;
+        }
+      }
+    }
   }
 
   // ---- K tile staging: each wave issues SEG_PER_WAVE wave-wide 128-bit loads that land in LDS
@@ -364,13 +397,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
 #pragma unroll
             for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
             // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
-            int hh_, iobs;
-            decode_row(d, A.g, rs, (rb * NW + wv) * 32 + l32, &hh_, &iobs);
-            const int last = iobs < d.w ? m + iobs : n_s - 1;     // last visible key of this row
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               const int key = tk0 + kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-              if (key > last) acc[i] = -INFINITY;
+              if (key > last1[rb]) acc[i] = -INFINITY;
             }
             float tmax = acc[0];
 #pragma unroll
@@ -398,12 +428,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) p[i] = __builtin_amdgcn_exp2f(fmaf(acc[i], c2, nlse[rb][i]));
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              int hh_, iobs;
-              decode_row(d, A.g, rs, (rb * NW + wv) * 32 + 8 * (i >> 2) + 4 * half + (i & 3), &hh_, &iobs);
-              const int last = iobs < d.w ? m + iobs : n_s - 1;
-              if (key > last) p[i] = 0.f;
-            }
+            for (int i = 0; i < 16; ++i)
+              if (key > last2[rb][i]) p[i] = 0.f;
             if (RED == 0) {
 #pragma unroll
               for (int i = 0; i < 16; ++i) colsum += p[i];
@@ -446,6 +472,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   }
 }
 
+#undef SPECKV_ROW_VALID
 #undef SPECKV_LOAD_TILE
 #undef SPECKV_LOAD_BFRAG
 #undef SPECKV_FLUSH_TILE
