@@ -105,6 +105,8 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_all_kernel(
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelPerThread = 4;
+constexpr int kHistCopies = 8;
+constexpr int kHistUnroll = 8;     // independent loads in flight per thread in the histogram passes
 
 // Order-preserving map float -> uint32 (larger float, larger key); -0 counts as +0.
 __device__ inline uint32_t order_key(float f) {
@@ -114,14 +116,14 @@ __device__ inline uint32_t order_key(float f) {
 }
 
 struct SelShared {
-  uint32_t hist[2048];
+  uint32_t hist[kHistCopies * 2048];   // one copy per lane residue: spreads atomics that hit one bin
   uint32_t wave_tot[2][kSelWaves];
   uint32_t prefix, remaining;
 };
 
 // Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
 // Uses wavefront shuffles for the in-wave scan and LDS for the 16 wave totals.
-__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total) {
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t inc = v;
 #pragma unroll
@@ -144,25 +146,38 @@ __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, 
 
 // Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
 // equal values taken from the low-index end.
-__device__ void select_top_row(const float *__restrict__ x, int m, int count,
+__device__ __forceinline__ void select_top_row(const float *__restrict__ x, int m, int count,
                                int32_t *__restrict__ out, SelShared &sh) {
   const int tid = threadIdx.x;
   uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
-  const int shifts[3] = {21, 10, 0};
-  const int nbins[3] = {2048, 2048, 1024};
+#pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
-    const int shift = shifts[pass], nb = nbins[pass];
-    for (int b = tid; b < 2048; b += kSelThreads) sh.hist[b] = 0;
+    const int shift = pass == 0 ? 21 : pass == 1 ? 10 : 0;       // digits of 11, 11 and 10 bits
+    const int nb = pass == 2 ? 1024 : 2048;
+    for (int b = tid; b < kHistCopies * 2048; b += kSelThreads) sh.hist[b] = 0;
     __syncthreads();
-    for (int j = tid; j < m; j += kSelThreads) {
-      const uint32_t key = order_key(x[j]);
-      if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
+    // the loads are unconditional (index clamped) so that kHistUnroll of them are in flight
+    for (int j0 = 0; j0 < m; j0 += kSelThreads * kHistUnroll) {
+      float val[kHistUnroll];
+#pragma unroll
+      for (int u = 0; u < kHistUnroll; ++u) val[u] = x[min(j0 + u * kSelThreads + tid, m - 1)];
+#pragma unroll
+      for (int u = 0; u < kHistUnroll; ++u) {
+        const uint32_t key = order_key(val[u]);
+        if (j0 + u * kSelThreads + tid < m && (key & mask) == prefix)
+          atomicAdd(&sh.hist[(tid % kHistCopies) * 2048 + ((key >> shift) & (nb - 1))], 1u);
+      }
     }
     __syncthreads();
     // thread t owns the bins nb-1-2t and nb-2-2t: scanning threads in order walks the
     // bins from the largest digit down.
     const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
-    const uint32_t c0 = b0 >= 0 ? sh.hist[b0] : 0u, c1 = b1 >= 0 ? sh.hist[b1] : 0u;
+    uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+    for (int cp = 0; cp < kHistCopies; ++cp) {
+      if (b0 >= 0) c0 += sh.hist[cp * 2048 + b0];
+      if (b1 >= 0) c1 += sh.hist[cp * 2048 + b1];
+    }
     uint32_t total;
     const uint32_t above = block_exclusive_scan(c0 + c1, sh.wave_tot[0], &total);
     if (above < remaining && remaining <= above + c0) {
@@ -183,16 +198,20 @@ __device__ void select_top_row(const float *__restrict__ x, int m, int count,
   const uint32_t thr = prefix, need_eq = remaining;
   uint32_t run_gt = 0, run_eq = 0;
   int buf = 0;
+  // the values of the next tile are requested before the current tile is ranked
+  float val[kSelPerThread], nxt[kSelPerThread];
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e) val[e] = x[min(tid * kSelPerThread + e, m - 1)];
   for (int j0 = 0; j0 < m; j0 += kSelThreads * kSelPerThread, buf ^= 1) {
     const int jb = j0 + tid * kSelPerThread;
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) nxt[e] = x[min(jb + kSelThreads * kSelPerThread + e, m - 1)];
     uint32_t gt_bits = 0, eq_bits = 0, cg = 0, ce = 0;
 #pragma unroll
     for (int e = 0; e < kSelPerThread; ++e) {
-      if (jb + e < m) {
-        const uint32_t key = order_key(x[jb + e]);
-        if (key > thr) { gt_bits |= 1u << e; ++cg; }
-        if (key == thr) { eq_bits |= 1u << e; ++ce; }
-      }
+      const uint32_t key = order_key(val[e]);
+      if (jb + e < m && key > thr) { gt_bits |= 1u << e; ++cg; }
+      if (jb + e < m && key == thr) { eq_bits |= 1u << e; ++ce; }
     }
     // one scan for both counts: gt in the low 16 bits, eq in the high 16 bits
     // (a tile holds at most 4096 entries, so neither field can overflow)
@@ -208,6 +227,8 @@ __device__ void select_top_row(const float *__restrict__ x, int m, int count,
     }
     run_gt += total & 0xffffu;
     run_eq += total >> 16;
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) val[e] = nxt[e];
   }
 }
 
