@@ -463,3 +463,24 @@ def test_scores_with_supplied_row_normalisers(S, shift):
     S.speckv_select(p, pooled, idx2)
     torch.cuda.synchronize()
     assert torch.equal(idx, idx2)
+
+
+def test_many_short_sequences(S):
+    """The maximum of 128 sequences in one call, most of them shorter than one key tile."""
+    rng = np.random.default_rng(61)
+    lens = tuple(int(x) for x in rng.integers(40, 400, size=128))
+    w = workloads.SpecKVWorkload(
+        name="many", n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, seq_lens=lens, n_window=8,
+        n_lookahead=8, pool_k=7, c_max=20, dtype="bf16", sm_scale=0.125, n_planted=2,
+        channel_scale=(0.5, 4.0), seed=62)
+    check_full_path(S, w)
+
+
+def test_largest_row_group(S):
+    """G * R at the documented limit of 4096 rows per KV head (8 row super-blocks)."""
+    w = workloads.SpecKVWorkload(
+        name="rows4096", n_layers=1, n_q_heads=16, n_kv_heads=1, head_dim=128, seq_lens=(600,),
+        n_window=100, n_lookahead=156, pool_k=7, c_max=50, dtype="bf16", sm_scale=1 / math.sqrt(128),
+        n_planted=4, channel_scale=(0.5, 4.0), seed=63)
+    check_full_path(S, w)
+    check_full_path(S, w, reduce="max", pool="avg")
