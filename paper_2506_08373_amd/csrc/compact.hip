@@ -2,15 +2,15 @@
 //
 // Pure gather, bound by HBM bandwidth.  One launch covers every layer, sequence and KV
 // head, K and V together.  A row of d elements is moved by rowbytes/16 adjacent lanes,
-// each with one 128-bit load and one 128-bit store; every thread keeps UNROLL rows in
-// flight before it stores, so a wave has several KiB outstanding.
+// each with one non-temporal 128-bit load and store per tensor.  One row per thread group
+// measured best (occupancy hides the latency; more rows per thread only cost registers).
 #include "speckv_internal.h"
 
 namespace speckv {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 1;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
 
