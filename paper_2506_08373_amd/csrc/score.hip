@@ -601,10 +601,6 @@ hipError_t dispatch_geom(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   const int code = A.g.NW * 10 + A.g.MB;
   switch (code) {
     case 41: return launch_passes<ELT, D, 1, 4>(A, st, ev);
-    case 42: return launch_passes<ELT, D, 2, 4>(A, st, ev);
-    case 44:
-      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 4, 4>(A, st, ev);
-      return hipErrorInvalidValue;
     case 81: return launch_passes<ELT, D, 1, 8>(A, st, ev);
     case 82:
       if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 2, 8>(A, st, ev);
