@@ -21,8 +21,7 @@ pool kernel k, budget C_max, m = n_in - n_window):
 * grouped-query attention: the scores of the query heads that share a KV head
   are combined into one score per KV head (App. C.2, the GQA note).
 
-Readings taken where the paper is silent or at odds with itself (each is listed
-with its reason in the design notes of this repository):
+Readings taken where the paper is silent or at odds with itself:
 
 * by default the reduction over queries and over the heads of a group is a SUM
   (Eq. 1's mean times a constant); with reduce="max" (Alg. 1 MaxReduce step;
