@@ -517,3 +517,60 @@ def test_graph_capture_and_replay(S):
         torch.cuda.synchronize()
         assert torch.equal(got[0], idx) and torch.equal(got[1], k_out) and torch.equal(got[2], v_out)
         assert int(idx.min()) >= 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_select_fuzz_bit_exact(S, seed):
+    """Random ragged rows with heavy ties, negative and zero scores, budgets from 0 to beyond m:
+    selection on given fp32 scores is integer work and must equal the oracle exactly."""
+    rng = np.random.default_rng(1000 + seed)
+    n_seqs = 24
+    n_window = int(rng.integers(0, 40))
+    lens = tuple(int(x) for x in np.concatenate([rng.integers(max(1, n_window), 300, size=16),
+                                                 rng.integers(3000, 70000, size=n_seqs - 16)]))
+    c_max = int(rng.choice([0, 1, 7, 500, 4096, 100000]))
+    w = workloads.SpecKVWorkload(
+        name="fuzz", n_layers=2, n_q_heads=3, n_kv_heads=3, head_dim=64, seq_lens=lens,
+        n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+    p = make_params(S, w)
+    L, H, T = 2, 3, w.total_tokens
+    levels = int(rng.choice([2, 17, 1000, 10 ** 6]))
+    base = (rng.integers(0, levels, size=(L, H * T)).astype(np.float32) - levels // 3) / np.float32(levels)
+    pooled = torch.from_numpy(base).cuda()
+    KT = S.total_keep(p)
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    S.speckv_select(p, pooled, idx)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    for layer in range(L):
+        for s in range(n_seqs):
+            n = lens[s]
+            rows = split_scores(w, base, layer, s)
+            got = split_keep(w, idx_h, layer, s, c_max)
+            for g in range(H):
+                want = orc.keep_indices(rows[g, :n - n_window].astype(np.float64), n, n_window, c_max)
+                assert got[g].tolist() == want.tolist(), (seed, layer, s, g)
+
+
+def test_second_index_set_from_the_same_scores(S):
+    """Alg. 1 also takes i_vert = topk(s, n_vert) from the same pooled scores: scoring once and
+    selecting twice with different budgets gives both sets; the larger contains the smaller."""
+    w = workloads.llama8b_layer(n_in=6000, c_max=256, name="ivert")
+    t = workloads.generate(w)
+    p_cache = make_params(S, w, c_max=256)
+    p_vert = make_params(S, w, c_max=2048)
+    H, T = w.n_kv_heads, w.total_tokens
+    pooled = torch.empty((1, H * T), dtype=torch.float32, device="cuda")
+    S.speckv_score(p_cache, t["q"].cuda(), t["k"].cuda(), pooled, None, alloc_ws(S, p_cache))
+    idx_c = torch.empty((1, H * S.total_keep(p_cache)), dtype=torch.int32, device="cuda")
+    idx_v = torch.empty((1, H * S.total_keep(p_vert)), dtype=torch.int32, device="cuda")
+    S.speckv_select(p_cache, pooled, idx_c)
+    S.speckv_select(p_vert, pooled, idx_v)
+    torch.cuda.synchronize()
+    ic = idx_c.cpu().numpy().reshape(H, -1)
+    iv = idx_v.cpu().numpy().reshape(H, -1)
+    m = 6000 - w.n_window
+    pooled_h = pooled.cpu().numpy().reshape(H, 6000)
+    for g in range(H):
+        assert set(ic[g].tolist()) <= set(iv[g].tolist())
+        assert iv[g][:2048].tolist() == orc.select_top(pooled_h[g, :m], 2048).tolist()    # i_vert itself
