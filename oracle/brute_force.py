@@ -93,6 +93,37 @@ def best_subset_exhaustive(pooled: Sequence[float], count: int) -> List[int]:
     return list(best)
 
 
+def ada_head_counts(pooled: Sequence[Sequence[float]], count: int, floor: int) -> List[int]:
+    """Shared layer budget: each head's best min(floor, count) first, then the best of the rest
+    of the layer by (-value, head, index) until Hkv * count are kept."""
+    H, m = len(pooled), len(pooled[0])
+    f = min(floor, count)
+    taken = set()
+    for h in range(H):
+        for j in sorted(range(m), key=lambda j: (-pooled[h][j], j))[:f]:
+            taken.add((h, j))
+    rest = sorted(((h, j) for h in range(H) for j in range(m) if (h, j) not in taken),
+                  key=lambda hj: (-pooled[hj[0]][hj[1]], hj[0], hj[1]))[:H * (count - f)]
+    counts = [f] * H
+    for h, _ in rest:
+        counts[h] += 1
+    return counts
+
+
+def best_allocation_exhaustive(pooled: Sequence[Sequence[float]], count: int, floor: int) -> float:
+    """Largest total score any allocation (n_0..n_{H-1}), n_h >= min(floor, count), sum = H * count,
+    can keep when head h keeps its n_h best candidates."""
+    H, m = len(pooled), len(pooled[0])
+    f = min(floor, count)
+    ranked = [sorted(row, reverse=True) for row in pooled]
+    best = -math.inf
+    for alloc in itertools.product(range(f, m + 1), repeat=H):
+        if sum(alloc) != H * count:
+            continue
+        best = max(best, math.fsum(math.fsum(ranked[h][:alloc[h]]) for h in range(H)))
+    return best
+
+
 def speckv_layer(q, k, v, n_window: int, pool_k: int, c_max: int, sm_scale: float,
                  reduce: str = "sum", pool: str = "max"):
     n, Hkv = len(k), len(k[0])

@@ -39,7 +39,15 @@ Readings taken where the paper is silent or at odds with itself:
 * the budget ``c_max`` counts NON-window keys: C = min(c_max, m) are selected
   and all n_window window keys are appended, so C + n_window are kept;
 * equal pooled scores at the boundary: the smaller index wins;
-* kept indices are emitted in ascending order (window last).
+* kept indices are emitted in ascending order (window last);
+* per-head budgets (App. "Integration and Comparison with the AdaKV Baseline"
+  only says that a different budget per attention head is applied to SpecKV as
+  that baseline does; no formula): per (sequence, layer) every KV head first
+  keeps its own best min(floor, C) candidates, then the remaining
+  Hkv*C - Hkv*min(floor, C) slots go to the best remaining candidates of the
+  whole layer whatever their head (ties: smaller head, then smaller index).
+  The layer keeps Hkv*C non-window keys in total, as with equal budgets.  The
+  exact safeguard the authors used is UNPINNED.
 
 Parity with the authors' own implementation is UNPINNED: the paper prints no
 numeric example for this path.  The functions below are pinned instead by
@@ -198,9 +206,44 @@ def keep_indices(pooled_row: np.ndarray, n_in: int, n_window: int, c_max: int) -
     return np.concatenate([select_top(pooled_row, C), np.arange(m, n_in, dtype=np.int64)])
 
 
+def ada_head_counts(pooled: np.ndarray, count: int, floor: int) -> np.ndarray:
+    """Non-window keys kept per KV head when a layer shares its budget across heads.
+
+    pooled [Hkv, m]; `count` = C, the per-head budget if it were equal; every head
+    keeps at least min(floor, C).  Returns n[Hkv] with sum Hkv * C.
+    (App. "Integration and Comparison with the AdaKV Baseline"; rule: see header.)
+    """
+    pooled = np.asarray(pooled, dtype=np.float64)
+    Hkv, m = pooled.shape
+    f = min(floor, count)
+    guaranteed = np.zeros((Hkv, m), dtype=bool)
+    for g in range(Hkv):
+        guaranteed[g, select_top(pooled[g], f)] = True
+    heads, cols = np.nonzero(~guaranteed)                     # head-major, index ascending
+    order = np.argsort(-pooled[heads, cols], kind="stable")   # ties keep (head, index) order
+    extra = heads[order[:Hkv * (count - f)]]
+    return f + np.bincount(extra, minlength=Hkv).astype(np.int64)
+
+
+def ada_keep_indices(pooled: np.ndarray, n_in: int, n_window: int, c_max: int,
+                     floor: int) -> List[np.ndarray]:
+    """i_cache per KV head with shared budget: head g keeps its top n[g], then the window."""
+    m = n_in - n_window
+    if pooled.shape[-1] != m:
+        raise ValueError("pooled must hold the m non-window candidates")
+    counts = ada_head_counts(pooled, min(c_max, m), floor)
+    window = np.arange(m, n_in, dtype=np.int64)
+    return [np.concatenate([select_top(pooled[g], int(counts[g])), window]) for g in range(pooled.shape[0])]
+
+
 # --------------------------------------------------------------------------- #
 # Compaction (Alg. 1 last step)
 # --------------------------------------------------------------------------- #
+def compact_ragged(x: np.ndarray, idx: Sequence[np.ndarray]) -> np.ndarray:
+    """x [n, Hkv, d], idx[g] of any length -> rows x[idx[g], g, :] of head 0, 1, ... stacked."""
+    return np.concatenate([x[idx[g], g, :] for g in range(x.shape[1])], axis=0)
+
+
 def compact(x: np.ndarray, idx: np.ndarray) -> np.ndarray:
     """x [n, Hkv, d], idx [Hkv, n_keep] -> out [Hkv, n_keep, d] = x[idx[g, r], g, :]."""
     Hkv = x.shape[1]
@@ -223,6 +266,21 @@ def speckv_layer(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window
     out = {"raw": raw, "pooled": pooled, "idx": idx, "k_out": compact(k, idx)}
     if v is not None:
         out["v_out"] = compact(v, idx)
+    return out
+
+
+def speckv_layer_ada(q: np.ndarray, k: np.ndarray, v: Optional[np.ndarray], n_window: int,
+                     pool_k: int, c_max: int, floor: int, sm_scale: float, reduce: str = "sum",
+                     pool: str = "max") -> Dict[str, object]:
+    """One (sequence, layer) with the layer's budget shared across its KV heads."""
+    n = k.shape[0]
+    raw = raw_scores(q, k, n_window, sm_scale, reduce=reduce)
+    pooled = pooled_scores(raw, n_window, pool_k, pool=pool)
+    idx = ada_keep_indices(pooled, n, n_window, c_max, floor)
+    head_off = np.concatenate([[0], np.cumsum([len(i) for i in idx])]).astype(np.int64)
+    out = {"raw": raw, "pooled": pooled, "idx": idx, "head_off": head_off, "k_out": compact_ragged(k, idx)}
+    if v is not None:
+        out["v_out"] = compact_ragged(v, idx)
     return out
 
 

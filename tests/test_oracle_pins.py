@@ -502,3 +502,77 @@ def test_supplied_lse_reduces_to_the_default_and_scales():
     # masked entries stay zero with a supplied normaliser
     P = orc.attention_probs(q[:, 0], k[:, 0], pos, 0.6, lse[:, 0])
     assert P[0, n - 1] == 0.0 and P[w, n - 1] > 0.0
+
+
+# --------------------------------------------------------------------------- #
+# Shared layer budget across KV heads (App. "Integration and Comparison with the AdaKV Baseline")
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("seed", range(6))
+def test_ada_counts_match_brute_force_and_invariants(seed):
+    rng = np.random.default_rng(seed)
+    H, m = int(rng.integers(1, 5)), int(rng.integers(4, 40))
+    count = int(rng.integers(0, m + 1))
+    floor = int(rng.integers(0, count + 3))
+    levels = int(rng.choice([3, 10, 10 ** 6]))                    # heavy ties included
+    pooled = rng.integers(0, levels, size=(H, m)).astype(np.float64) / levels
+    got = orc.ada_head_counts(pooled, count, floor)
+    assert got.tolist() == bf.ada_head_counts(pooled.tolist(), count, floor)
+    assert got.sum() == H * count
+    assert got.min() >= min(floor, count) and got.max() <= m
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_ada_allocation_keeps_the_largest_total_score(seed):
+    """The rule is the allocation that maximises the retained pooled mass under the floor:
+    checked against every allocation on small inputs."""
+    rng = np.random.default_rng(100 + seed)
+    H, m = 3, 7
+    count = int(rng.integers(1, 6))
+    floor = int(rng.integers(0, count + 1))
+    pooled = rng.random((H, m))
+    counts = orc.ada_head_counts(pooled, count, floor)
+    kept = sum(np.sort(pooled[h])[::-1][:counts[h]].sum() for h in range(H))
+    assert kept == pytest.approx(bf.best_allocation_exhaustive(pooled.tolist(), count, floor), rel=1e-12)
+
+
+def test_ada_floor_extremes_reduce_to_plain_selections():
+    rng = np.random.default_rng(7)
+    H, m, count, w = 4, 50, 9, 3
+    pooled = rng.random((H, m))
+    # floor = C: equal budgets, the ordinary per-head selection
+    idx = orc.ada_keep_indices(pooled, m + w, w, count, floor=count)
+    for g in range(H):
+        assert idx[g].tolist() == orc.keep_indices(pooled[g], m + w, w, count).tolist()
+    # floor = 0: the H*C largest entries of the layer (library sort of the flattened scores)
+    idx0 = orc.ada_keep_indices(pooled, m + w, w, count, floor=0)
+    flat_top = np.argsort(-pooled.reshape(-1), kind="stable")[:H * count]
+    want = sorted((int(t) // m, int(t) % m) for t in flat_top)
+    got = sorted((g, int(j)) for g in range(H) for j in idx0[g][:-w])
+    assert got == want
+
+
+def test_ada_tie_rule_prefers_smaller_head_then_index():
+    pooled = np.array([[1.0, 0.5, 0.5, 0.0], [0.5, 0.5, 0.9, 0.0]])
+    # C = 2 per head, floor 1: floors are (0,0) and (1,2); two more slots among the 0.5 ties
+    counts = orc.ada_head_counts(pooled, 2, 1)
+    assert counts.tolist() == [3, 1]
+    idx = orc.ada_keep_indices(pooled, 4, 0, 2, 1)
+    assert idx[0].tolist() == [0, 1, 2] and idx[1].tolist() == [2]
+
+
+def test_ada_layer_end_to_end_against_brute_force():
+    w = workloads.SpecKVWorkload(name="ada_tiny", n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=8,
+                                 seq_lens=(40,), n_window=4, n_lookahead=3, pool_k=3, c_max=6,
+                                 dtype="f32", sm_scale=0.5, n_planted=2)
+    t = workloads.generate(w)
+    q, k, v = (workloads.to_float64(t[x][0]) for x in ("q", "k", "v"))
+    q = q[0]
+    out = orc.speckv_layer_ada(q, k, v, 4, 3, 6, 2, 0.5)
+    ref = bf.speckv_layer(q.tolist(), k.tolist(), v.tolist(), 4, 3, 6, 0.5)
+    counts = bf.ada_head_counts(ref["pooled"], 6, 2)
+    assert [len(i) - 4 for i in out["idx"]] == counts
+    assert out["head_off"].tolist() == [0, counts[0] + 4, counts[0] + counts[1] + 8]
+    for g in range(2):
+        assert out["idx"][g][:-4].tolist() == bf.select_top(ref["pooled"][g], counts[g])
+    rows = np.concatenate([k[out["idx"][g], g, :] for g in range(2)])
+    assert np.array_equal(out["k_out"], rows)
