@@ -173,6 +173,36 @@ speckv_status speckv_compress_events(const speckv_params *p, const void *q, cons
                                      void *workspace, size_t workspace_bytes, void *stream,
                                      void **events, int32_t n_events);
 
+/* Per-head budgets (App. "Integration and Comparison with the AdaKV Baseline": a different
+ * budget per attention head, applied to SpecKV).  The paper gives no formula; the rule here is:
+ * per (layer, sequence), with C = min(c_max, m) and f = min(c_floor, C), every KV head keeps
+ * its own f best candidates, and the remaining Hkv*(C - f) slots go to the best remaining
+ * candidates of the whole layer whatever their head (equal scores: smaller head, then smaller
+ * index).  A layer keeps Hkv*C non-window keys, as with equal budgets, so idx, k_out and v_out
+ * have the sizes of the equal-budget calls; only the split between heads moves.
+ *   head_off  int32 device, [n_layers][n_seqs][n_kv_heads + 1]: row offsets of the heads inside
+ *             their (layer, sequence) block; head g owns rows head_off[g] .. head_off[g+1]-1,
+ *             its kept candidates ascending followed by the window; head_off[Hkv] = Hkv*n_keep_s.
+ *   idx       per layer: sequence s starts at Hkv*KT_before(s) as in the "idx" layout; inside
+ *             the block the heads follow each other at head_off.
+ *   k_out / v_out  rows in the same order as idx, each d elements.
+ * c_floor >= c_max gives exactly speckv_select's result.  Needs n_kv_heads <=
+ * SPECKV_MAX_ADA_HEADS and a workspace of speckv_ada_workspace_bytes (0 if the parameters are
+ * invalid), which covers all three calls.  `pooled` must not hold NaN. */
+#define SPECKV_MAX_ADA_HEADS 128
+size_t speckv_ada_workspace_bytes(const speckv_params *p);
+speckv_status speckv_select_ada(const speckv_params *p, int32_t c_floor, const float *pooled,
+                                int32_t *idx, int32_t *head_off, void *workspace,
+                                size_t workspace_bytes, void *stream);
+speckv_status speckv_compact_ada(const speckv_params *p, const void *k, const void *v,
+                                 const int32_t *idx, const int32_t *head_off, void *k_out,
+                                 void *v_out, void *stream);
+/* score -> shared-budget selection -> compaction in one call (see speckv_compress). */
+speckv_status speckv_compress_ada(const speckv_params *p, int32_t c_floor, const void *q,
+                                  const void *k, const void *v, int32_t *idx, int32_t *head_off,
+                                  void *k_out, void *v_out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* Prompt-token selection from draft-model attention (Sec. 4.2 / Alg. 2, in the reduced
  * form: sum instead of max aggregation, no row weights, no skipped layers).  Needs
  * n_seqs == 1.  score[j] = attention probability summed over all layers, heads and

@@ -15,7 +15,11 @@ from .binding import (  # noqa: F401
     specpc_compress_workspace_bytes,
     specpc_select_tokens,
     specpc_workspace_bytes,
+    ada_workspace_bytes,
     speckv_compact,
+    speckv_compact_ada,
+    speckv_compress_ada,
+    speckv_select_ada,
     speckv_compress,
     speckv_compress_events,
     speckv_compress_lse,

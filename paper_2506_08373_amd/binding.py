@@ -46,7 +46,8 @@ EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv
            "speckv_score", "speckv_select", "speckv_compact", "speckv_compress",
            "speckv_compress_events", "speckv_score_lse", "speckv_compress_lse",
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
-           "specpc_compress_prompt")
+           "specpc_compress_prompt", "speckv_ada_workspace_bytes", "speckv_select_ada",
+           "speckv_compact_ada", "speckv_compress_ada")
 
 
 def library_path() -> str:
@@ -88,6 +89,15 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_compress_events.restype = ctypes.c_int
     lib.speckv_compress_events.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp,
                                            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
+    lib.speckv_ada_workspace_bytes.restype = ctypes.c_size_t
+    lib.speckv_ada_workspace_bytes.argtypes = [P]
+    lib.speckv_select_ada.restype = ctypes.c_int
+    lib.speckv_select_ada.argtypes = [P, ctypes.c_int32, f32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_compact_ada.restype = ctypes.c_int
+    lib.speckv_compact_ada.argtypes = [P, vp, vp, i32p, i32p, vp, vp, vp]
+    lib.speckv_compress_ada.restype = ctypes.c_int
+    lib.speckv_compress_ada.argtypes = [P, ctypes.c_int32, vp, vp, vp, i32p, i32p, vp, vp, vp,
+                                        ctypes.c_size_t, vp]
     lib.specpc_select_tokens.restype = ctypes.c_int
     lib.specpc_select_tokens.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
                                          i32p, vp, ctypes.c_size_t, vp]
@@ -234,6 +244,34 @@ def speckv_compress(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace) -> N
                                           _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
                                           _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
                                           wp, wb, _stream()), "speckv_compress")
+
+
+def ada_workspace_bytes(p: SpecKVParams) -> int:
+    return int(load_library().speckv_ada_workspace_bytes(p.ref()))
+
+
+def speckv_select_ada(p: SpecKVParams, c_floor: int, pooled, idx, head_off, workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_select_ada(p.ref(), int(c_floor), _ptr(pooled, torch.float32),
+                                            _ptr(idx, torch.int32), _ptr(head_off, torch.int32),
+                                            wp, wb, _stream()), "speckv_select_ada")
+
+
+def speckv_compact_ada(p: SpecKVParams, k, v, idx, head_off, k_out, v_out) -> None:
+    _check(load_library().speckv_compact_ada(p.ref(), _ptr(k, p.torch_dtype), _ptr(v, p.torch_dtype),
+                                             _ptr(idx, torch.int32), _ptr(head_off, torch.int32),
+                                             _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
+                                             _stream()), "speckv_compact_ada")
+
+
+def speckv_compress_ada(p: SpecKVParams, c_floor: int, q, k, v, idx, head_off, k_out, v_out,
+                        workspace) -> None:
+    wp, wb = _ws(workspace)
+    _check(load_library().speckv_compress_ada(p.ref(), int(c_floor), _ptr(q, p.torch_dtype),
+                                              _ptr(k, p.torch_dtype), _ptr(v, p.torch_dtype),
+                                              _ptr(idx, torch.int32), _ptr(head_off, torch.int32),
+                                              _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
+                                              wp, wb, _stream()), "speckv_compress_ada")
 
 
 N_STAGE_EVENTS = 7

@@ -127,6 +127,9 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   pl->off_pooled2 = take(one_row_per_call ? (size_t)d.T * sizeof(float) : 0);
   pl->off_sel = take(one_row_per_call ? (size_t)(top_k > 0 ? top_k : 0) * sizeof(int32_t) : 0);
   pl->total = off;
+  pl->off_ada_hist = take((size_t)d.L * d.S * d.Hkv * 2048 * sizeof(uint32_t));
+  pl->off_ada_state = take((size_t)d.L * d.S * (2 + 2 * (size_t)d.Hkv) * sizeof(uint32_t));
+  pl->total_ada = off;
   return SPECKV_OK;
 }
 
@@ -281,6 +284,74 @@ speckv_status speckv_compress_events(const speckv_params *p, const void *q, cons
     if (events[i] == nullptr) return SPECKV_ERR_INVALID_ARG;
   return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream,
                        reinterpret_cast<hipEvent_t *>(events));
+}
+
+size_t speckv_ada_workspace_bytes(const speckv_params *p) {
+  Plan pl;
+  if (build_plan(p, &pl, false, 0) != SPECKV_OK || pl.d.Hkv > SPECKV_MAX_ADA_HEADS) return 0;
+  return pl.total_ada;
+}
+
+static speckv_status ada_plan(const speckv_params *p, int32_t c_floor, Plan *pl) {
+  speckv_status st = build_plan(p, pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (c_floor < 0) return SPECKV_ERR_INVALID_ARG;
+  if (pl->d.Hkv > SPECKV_MAX_ADA_HEADS) return SPECKV_ERR_UNSUPPORTED;
+  return SPECKV_OK;
+}
+
+speckv_status speckv_select_ada(const speckv_params *p, int32_t c_floor, const float *pooled, int32_t *idx,
+                                int32_t *head_off, void *workspace, size_t workspace_bytes, void *stream) {
+  Plan pl;
+  speckv_status st = ada_plan(p, c_floor, &pl);
+  if (st != SPECKV_OK) return st;
+  if (pooled == nullptr || idx == nullptr || head_off == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(pooled) & 3u) || (reinterpret_cast<uintptr_t>(idx) & 3u) ||
+      (reinterpret_cast<uintptr_t>(head_off) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+      workspace_bytes < pl.total_ada) return SPECKV_ERR_WORKSPACE;
+  char *ws = static_cast<char *>(workspace);
+  return from_hip(launch_select_ada(pl, c_floor, pooled, idx, head_off,
+                                    reinterpret_cast<uint32_t *>(ws + pl.off_ada_hist),
+                                    reinterpret_cast<uint32_t *>(ws + pl.off_ada_state),
+                                    static_cast<hipStream_t>(stream)));
+}
+
+speckv_status speckv_compact_ada(const speckv_params *p, const void *k, const void *v, const int32_t *idx,
+                                 const int32_t *head_off, void *k_out, void *v_out, void *stream) {
+  Plan pl;
+  speckv_status st = ada_plan(p, 0, &pl);
+  if (st != SPECKV_OK) return st;
+  if (k == nullptr || idx == nullptr || head_off == nullptr || k_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((v == nullptr) != (v_out == nullptr)) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+      (reinterpret_cast<uintptr_t>(idx) & 3u) || (reinterpret_cast<uintptr_t>(head_off) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  return from_hip(launch_compact_ada(pl, k, v, idx, head_off, k_out, v_out, static_cast<hipStream_t>(stream)));
+}
+
+speckv_status speckv_compress_ada(const speckv_params *p, int32_t c_floor, const void *q, const void *k,
+                                  const void *v, int32_t *idx, int32_t *head_off, void *k_out, void *v_out,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  Plan pl;
+  speckv_status st = ada_plan(p, c_floor, &pl);
+  if (st != SPECKV_OK) return st;
+  if (q == nullptr || k == nullptr || idx == nullptr || head_off == nullptr || k_out == nullptr) return SPECKV_ERR_INVALID_ARG;
+  if ((v == nullptr) != (v_out == nullptr)) return SPECKV_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+      (reinterpret_cast<uintptr_t>(idx) & 3u) || (reinterpret_cast<uintptr_t>(head_off) & 3u)) return SPECKV_ERR_INVALID_ARG;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+      workspace_bytes < pl.total_ada) return SPECKV_ERR_WORKSPACE;
+  char *ws = static_cast<char *>(workspace);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
+  float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
+  hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+  if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_select_ada(pl, c_floor, pooled, idx, head_off, reinterpret_cast<uint32_t *>(ws + pl.off_ada_hist),
+                             reinterpret_cast<uint32_t *>(ws + pl.off_ada_state), hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return from_hip(launch_compact_ada(pl, k, v, idx, head_off, k_out, v_out, hs));
 }
 
 speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,

@@ -258,6 +258,170 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__
 }
 
 // ----------------------------------------------------------------------------------
+// layer budget shared across KV heads
+// ----------------------------------------------------------------------------------
+// The heads' counts follow from one layer-wide threshold: the largest key t for which
+//   F(t) = sum over heads of max(0, #{keys of the head >= t} - floor)
+// still reaches the number of slots left after the floors.  t is found digit by digit like
+// the per-row radix select, with one histogram per head (kept in the workspace) and a small
+// decision kernel per digit.  Search state per (layer, sequence): [0] prefix of t,
+// [2 .. 2+Hkv) keys above the prefix per head, [2+Hkv .. 2+2Hkv) keys equal to t per head.
+__device__ __forceinline__ int ada_shift(int level) { return level == 0 ? 21 : level == 1 ? 10 : 0; }
+__device__ __forceinline__ int ada_bins(int level) { return level == 2 ? 1024 : 2048; }
+
+__global__ __launch_bounds__(kSelThreads) void ada_hist_kernel(Dims d, SeqTab t,
+                                                               const float *__restrict__ pooled, int level,
+                                                               const uint32_t *__restrict__ state,
+                                                               uint32_t *__restrict__ hist) {
+  __shared__ SelShared sh;
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x;
+  const int g = unit % d.Hkv;
+  const int ls = unit / d.Hkv;
+  const int s = ls % d.S;
+  const int layer = ls / d.S;
+  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int m = n_s - d.w;
+  const float *x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  const int shift = ada_shift(level), nb = ada_bins(level);
+  const uint32_t mask = level == 0 ? 0u : level == 1 ? 0xffe00000u : 0xfffffc00u;
+  const uint32_t prefix = level == 0 ? 0u : state[(int64_t)ls * (2 + 2 * d.Hkv)];
+  for (int b = tid; b < kHistCopies * 2048; b += kSelThreads) sh.hist[b] = 0;
+  __syncthreads();
+  for (int j0 = 0; j0 < m; j0 += kSelThreads * kHistUnroll) {
+    float val[kHistUnroll];
+#pragma unroll
+    for (int u = 0; u < kHistUnroll; ++u) val[u] = x[min(j0 + u * kSelThreads + tid, m - 1)];
+#pragma unroll
+    for (int u = 0; u < kHistUnroll; ++u) {
+      const uint32_t key = order_key(val[u]);
+      if (j0 + u * kSelThreads + tid < m && (key & mask) == prefix)
+        atomicAdd(&sh.hist[(tid % kHistCopies) * 2048 + ((key >> shift) & (nb - 1))], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t *out = hist + (int64_t)unit * 2048;
+  for (int b = tid; b < 2048; b += kSelThreads) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int cp = 0; cp < kHistCopies; ++cp) c += sh.hist[cp * 2048 + b];
+    out[b] = c;
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void ada_decide_kernel(Dims d, SeqTab t, int c_floor, int level,
+                                                                 uint32_t *__restrict__ state,
+                                                                 uint32_t *__restrict__ hist,
+                                                                 int32_t *__restrict__ head_off) {
+  __shared__ uint32_t wave_tot[kSelWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ls = blockIdx.x;
+  const int s = ls % d.S;
+  const int H = d.Hkv;
+  const int m = t.cu[s + 1] - t.cu[s] - d.w;
+  const int C = min(d.c_max, m);
+  const int f = min(c_floor, C);
+  const unsigned long long need = (unsigned long long)H * (unsigned)(C - f);
+  uint32_t *hs = hist + (int64_t)ls * H * 2048;
+  uint32_t *st = state + (int64_t)ls * (2 + 2 * H);
+  const int shift = ada_shift(level), nb = ada_bins(level);
+
+  // (i) each head's histogram becomes inclusive suffix sums (keys with this digit or a larger one)
+  const int per = nb / 64;
+  for (int h = wave; h < H; h += kSelWaves) {
+    uint32_t *hh = hs + (int64_t)h * 2048 + lane * per;
+    uint32_t v[32];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 31; i >= 0; --i) {
+      if (i < per) { sum += hh[i]; v[i] = sum; }
+    }
+    uint32_t run = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t up = __shfl_down(run, off, 64);
+      if (lane + off < 64) run += up;
+    }
+    const uint32_t higher = run - sum;
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+      if (i < per) hh[i] = v[i] + higher;
+  }
+  __syncthreads();
+
+  // (ii) F at the digits nb-1-2t and nb-2-2t; F does not grow with the digit, so the digits
+  // that reach `need` are the lowest ones and their number gives the digit of t.
+  const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+  unsigned long long F0 = 0, F1 = 0;
+  if (b0 >= 0) {
+    for (int h = 0; h < H; ++h) {
+      const uint32_t above = level == 0 ? 0u : st[2 + h];
+      const uint32_t c0 = above + hs[(int64_t)h * 2048 + b0];
+      const uint32_t c1 = b1 >= 0 ? above + hs[(int64_t)h * 2048 + b1] : 0u;
+      F0 += c0 > (uint32_t)f ? c0 - (uint32_t)f : 0u;
+      F1 += c1 > (uint32_t)f ? c1 - (uint32_t)f : 0u;
+    }
+  }
+  const uint32_t hits = (b0 >= 0 && F0 >= need ? 1u : 0u) + (b1 >= 0 && F1 >= need ? 1u : 0u);
+  uint32_t n_hits;
+  (void)block_exclusive_scan(hits, wave_tot, &n_hits);
+  const int digit = (int)n_hits - 1;          // F(0) >= need always, so n_hits >= 1
+
+  // (iii) per head: keys above the extended prefix, and keys equal to it
+  if (tid < H) {
+    const uint32_t ge = hs[(int64_t)tid * 2048 + digit];
+    const uint32_t gt = digit + 1 < nb ? hs[(int64_t)tid * 2048 + digit + 1] : 0u;
+    st[2 + tid] = (level == 0 ? 0u : st[2 + tid]) + gt;
+    st[2 + H + tid] = ge - gt;
+  }
+  if (tid == 0) st[0] = (level == 0 ? 0u : st[0]) | ((uint32_t)digit << shift);
+  if (level < 2) return;
+  __syncthreads();
+  // (iv) t is complete: heads above their floor keep every key larger than t; the slots still
+  // open go to keys equal to t that no floor has taken, heads in order.
+  if (tid == 0) {
+    long long open = (long long)need;
+    for (int h = 0; h < H; ++h) {
+      const long long gt = st[2 + h];
+      open -= gt > f ? gt - f : 0;
+    }
+    int32_t *ho = head_off + (int64_t)ls * (H + 1);
+    int off = 0;
+    for (int h = 0; h < H; ++h) {
+      const long long gt = st[2 + h], eq = st[2 + H + h];
+      long long avail = gt + eq - f < eq ? gt + eq - f : eq;
+      if (avail < 0) avail = 0;
+      const long long take = avail < open ? avail : open;
+      open -= take;
+      ho[h] = off;
+      off += (int)((gt > f ? gt : f) + take) + d.w;
+    }
+    ho[H] = off;
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab t,
+                                                                 const float *__restrict__ pooled,
+                                                                 const int32_t *__restrict__ head_off,
+                                                                 int32_t *__restrict__ idx) {
+  __shared__ SelShared sh;
+  const int unit = blockIdx.x;
+  const int g = unit % d.Hkv;
+  const int ls = unit / d.Hkv;
+  const int s = ls % d.S;
+  const int layer = ls / d.S;
+  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int m = n_s - d.w;
+  const int32_t *ho = head_off + (int64_t)ls * (d.Hkv + 1);
+  const int start = ho[g];
+  const int count = min(max(ho[g + 1] - start - d.w, 0), m);
+  const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + start;
+  for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;
+  if (count > 0) select_top_row(row, m, count, out, sh);
+}
+
+// ----------------------------------------------------------------------------------
 // neighbour expansion (single workgroup)
 // ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelThreads) void expand_kernel(
@@ -350,6 +514,21 @@ hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipS
   const Dims &d = pl.d;
   const int64_t blocks = (int64_t)d.L * d.S * d.Hkv;
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kSelThreads), 0, st, d, pl.t, pooled, idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *pooled, int32_t *idx,
+                             int32_t *head_off, uint32_t *hist, uint32_t *state, hipStream_t st) {
+  const Dims &d = pl.d;
+  const unsigned pairs = (unsigned)(d.L * d.S);
+  for (int level = 0; level < 3; ++level) {
+    hipLaunchKernelGGL(ada_hist_kernel, dim3(pairs * d.Hkv), dim3(kSelThreads), 0, st, d, pl.t, pooled,
+                       level, state, hist);
+    hipLaunchKernelGGL(ada_decide_kernel, dim3(pairs), dim3(kSelThreads), 0, st, d, pl.t, c_floor, level,
+                       state, hist, head_off);
+  }
+  hipLaunchKernelGGL(select_ada_kernel, dim3(pairs * d.Hkv), dim3(kSelThreads), 0, st, d, pl.t, pooled,
+                     head_off, idx);
   return hipGetLastError();
 }
 

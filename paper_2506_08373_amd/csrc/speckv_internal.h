@@ -54,6 +54,7 @@ struct Plan {
   ScoreGeom g;
   // workspace carve-up (byte offsets, 256-aligned)
   size_t off_part, off_lse, off_planes, off_pooled, off_pooled2, off_sel, total;
+  size_t off_ada_hist, off_ada_state, total_ada;   // extra scratch of the shared-budget selection
 };
 
 inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -92,6 +93,12 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
 hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_window, int32_t pool_k,
                            hipStream_t st);
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st);
+// Shared layer budget: head offsets from a layer-wide threshold, then per-head selection.
+// hist: L*S*Hkv*2048 uint32, state: L*S*(2 + 2*Hkv) uint32 of scratch.
+hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *pooled, int32_t *idx,
+                             int32_t *head_off, uint32_t *hist, uint32_t *state, hipStream_t st);
+hipError_t launch_compact_ada(const Plan &pl, const void *k, const void *v, const int32_t *idx,
+                              const int32_t *head_off, void *k_out, void *v_out, hipStream_t st);
 hipError_t launch_select_row(const float *pooled_row, int32_t m, int32_t count, int32_t *sel,
                              hipStream_t st);
 hipError_t launch_expand(const int32_t *sel, int32_t count, int32_t n_in, int32_t n_window,

@@ -100,6 +100,22 @@ def test_null_misaligned_and_workspace_errors(lib):
     assert lib.speckv_compress_events(p.ref(), ok, ok, ok, ok, ok, ok, ok, need, None, None, 7) == -1
 
 
+def test_shared_budget_entry_points_validate(lib):
+    p = base_params()
+    ok = 256
+    need = S.ada_workspace_bytes(p)
+    assert need > S.workspace_bytes(p)
+    assert lib.speckv_select_ada(p.ref(), -1, ok, ok, ok, ok, need, None) == -1           # negative floor
+    assert lib.speckv_select_ada(p.ref(), 3, ok, ok, None, ok, need, None) == -1          # no head_off
+    assert lib.speckv_select_ada(p.ref(), 3, ok, ok, ok, ok, need - 1, None) == -3
+    assert lib.speckv_compact_ada(p.ref(), ok, ok, ok, None, ok, ok, None) == -1
+    assert lib.speckv_compress_ada(p.ref(), 3, ok, ok, ok, ok, ok, ok, ok, None, need, None) == -3
+    assert lib.speckv_compress_ada(p.ref(), 3, ok, ok, None, ok, ok, ok, ok, ok, need, None) == -1   # v_out without v
+    many = base_params(n_q_heads=256, n_kv_heads=256)
+    assert S.ada_workspace_bytes(many) == 0
+    assert lib.speckv_select_ada(many.ref(), 3, ok, ok, ok, ok, 1 << 40, None) == -2
+
+
 def test_binding_refuses_host_tensors(lib):
     p = base_params()
     x = torch.zeros(4)

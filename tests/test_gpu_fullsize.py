@@ -166,3 +166,60 @@ def test_specpc_full(S):
     lo = orc.expand_neighbors(np.nonzero(ref["pooled"] > tau + band)[0], n, w.n_window, nb)
     hi = orc.expand_neighbors(np.nonzero(ref["pooled"] >= tau - band)[0], n, w.n_window, nb)
     assert np.isin(lo, got).all() and np.isin(got, hi).all()
+
+
+def test_shared_layer_budget_128k(S):
+    """Per-head budgets (App. "Integration and Comparison with the AdaKV Baseline") at the 128K
+    shape: structure for every layer and head on the GPU, one whole layer against the oracle."""
+    w = workloads.llama8b_layer(n_in=131072, c_max=2048, n_layers=2, name="ada_128k")
+    c_floor = 410                                                         # a fifth of the budget
+    data = workloads.generate(w, device="cuda")
+    q, k, v = data["q"], data["k"], data["v"]
+    p = S.SpecKVParams.for_tensors(q, k, seq_lens=w.seq_lens, n_window=w.n_window, pool_k=w.pool_k,
+                                   c_max=w.c_max, sm_scale=w.sm_scale)
+    KT, L, H, d, G = S.total_keep(p), w.n_layers, w.n_kv_heads, w.head_dim, w.group
+    n, m = w.seq_lens[0], w.seq_lens[0] - w.n_window
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    head_off = torch.full((L, 1, H + 1), -1, dtype=torch.int32, device="cuda")
+    k_out = torch.empty((L, H * KT, d), dtype=w.torch_dtype, device="cuda")
+    v_out = torch.empty_like(k_out)
+    ws = torch.empty(S.ada_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    S.speckv_compress_ada(p, c_floor, q, k, v, idx, head_off, k_out, v_out, ws)
+    torch.cuda.synchronize()
+    off = head_off.cpu().numpy()[:, 0]
+    assert (off[:, 0] == 0).all() and (off[:, -1] == H * KT).all()
+    counts = np.diff(off, axis=1) - w.n_window
+    assert (counts >= c_floor).all() and (counts.sum(axis=1) == H * w.c_max).all()
+    assert (counts != w.c_max).any(), "the budgets did not move between heads: nothing was tested"
+    win = torch.arange(m, n, device="cuda")
+    for layer in range(L):
+        for g in range(H):
+            rows = idx[layer, off[layer, g]:off[layer, g + 1]].long()
+            assert bool((rows[1:] > rows[:-1]).all()) and bool((rows[-w.n_window:] == win).all())
+            planted = data["planted"][layer, 0, g]
+            assert bool((rows[:-w.n_window, None] == planted[None, :]).any(0).all())
+            assert torch.equal(k_out[layer, off[layer, g]:off[layer, g + 1]].view(torch.int16),
+                               k[layer, rows, g].view(torch.int16))
+            assert torch.equal(v_out[layer, off[layer, g]:off[layer, g + 1]].view(torch.int16),
+                               v[layer, rows, g].view(torch.int16))
+    # one whole layer through the oracle: the heads' scores, then the shared-budget rule
+    layer = 1
+    pooled = np.stack([
+        orc.pooled_scores(orc.raw_scores(workloads.to_float64(q[layer, 0, :, g * G:(g + 1) * G]),
+                                         workloads.to_float64(k[layer, :, g:g + 1]),
+                                         w.n_window, w.sm_scale), w.n_window, w.pool_k)[0]
+        for g in range(H)])
+    want = orc.ada_keep_indices(pooled, n, w.n_window, w.c_max, c_floor)
+    got = [idx[layer, off[layer, g]:off[layer, g + 1]].cpu().numpy().astype(np.int64) for g in range(H)]
+    if all(np.array_equal(a, b) for a, b in zip(got, want)):
+        return
+    # scores within the tolerance of the layer-wide threshold may fall either way
+    kept = np.concatenate([pooled[g][want[g][:-w.n_window]] for g in range(H)])
+    tau = kept.min()
+    band = REL_TOL * abs(tau) + ABS_FLOOR * pooled.max()
+    for g in range(H):
+        sel = got[g][:-w.n_window]
+        floor_tau = np.sort(pooled[g])[m - c_floor]                       # the head's own floor threshold
+        must = np.nonzero(pooled[g] > min(tau, floor_tau) + band)[0]
+        never = np.nonzero(pooled[g] < min(tau, floor_tau) - band)[0]
+        assert np.isin(must, sel).all() and not np.isin(never, sel).any()

@@ -574,3 +574,116 @@ def test_second_index_set_from_the_same_scores(S):
     for g in range(H):
         assert set(ic[g].tolist()) <= set(iv[g].tolist())
         assert iv[g][:2048].tolist() == orc.select_top(pooled_h[g, :m], 2048).tolist()    # i_vert itself
+
+
+# --------------------------------------------------------------------------- #
+# Layer budget shared across KV heads (App. "Integration and Comparison with the AdaKV Baseline")
+# --------------------------------------------------------------------------- #
+def ada_block(w, flat, layer, s, c_max, trailing=()):
+    """All Hkv*n_keep_s rows of one (layer, sequence) block of an idx / k_out style tensor."""
+    keeps = [min(c_max, n - w.n_window) + w.n_window for n in w.seq_lens]
+    ck = np.concatenate([[0], np.cumsum(keeps)])
+    a = w.n_kv_heads * ck[s]
+    return flat[layer, a:a + w.n_kv_heads * keeps[s]]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_select_ada_fuzz_bit_exact(S, seed):
+    """Selection with a shared layer budget on given fp32 scores is integer work: head offsets and
+    indices must equal the oracle's exactly (ties, negative scores, floors from 0 to beyond C)."""
+    rng = np.random.default_rng(2000 + seed)
+    n_seqs, H, L = 6, int(rng.choice([1, 3, 8])), 2
+    n_window = int(rng.integers(0, 20))
+    lens = tuple(int(x) for x in np.concatenate([rng.integers(max(1, n_window), 200, size=3),
+                                                 rng.integers(2000, 40000, size=n_seqs - 3)]))
+    c_max = int(rng.choice([0, 5, 300, 2048, 50000]))
+    c_floor = int(rng.choice([0, 1, c_max // 5, c_max, c_max + 7]))
+    w = workloads.SpecKVWorkload(
+        name="ada_fuzz", n_layers=L, n_q_heads=H, n_kv_heads=H, head_dim=64, seq_lens=lens,
+        n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+    p = make_params(S, w)
+    T = w.total_tokens
+    levels = int(rng.choice([3, 50, 10 ** 6]))
+    base = (rng.integers(0, levels, size=(L, H * T)).astype(np.float32) - levels // 4) / np.float32(levels)
+    # heads of very different sharpness so that the budgets really move between heads
+    for layer in range(L):
+        for s in range(n_seqs):
+            split_scores(w, base, layer, s)[...] *= np.float32(2.0) ** rng.integers(-3, 4, size=(H, 1))
+    pooled = torch.from_numpy(base).cuda()
+    KT = S.total_keep(p)
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    head_off = torch.full((L, n_seqs, H + 1), -1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(S.ada_workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
+    S.speckv_select_ada(p, c_floor, pooled, idx, head_off, ws)
+    torch.cuda.synchronize()
+    idx_h, off_h = idx.cpu().numpy(), head_off.cpu().numpy()
+    for layer in range(L):
+        for s in range(n_seqs):
+            n = lens[s]
+            rows = split_scores(w, base, layer, s)[:, :n - n_window].astype(np.float64)
+            want = orc.ada_keep_indices(rows, n, n_window, c_max, c_floor)
+            want_off = np.concatenate([[0], np.cumsum([len(x) for x in want])])
+            assert off_h[layer, s].tolist() == want_off.tolist(), (seed, layer, s)
+            got = ada_block(w, idx_h, layer, s, c_max)
+            assert got.tolist() == np.concatenate(want).tolist(), (seed, layer, s)
+
+
+def test_compress_ada_full_path(S):
+    """score -> shared-budget select -> compact in one call, against the oracle; the floor equal to
+    the budget reproduces the equal-budget call bit for bit."""
+    w = workloads.SpecKVWorkload(
+        name="ada_path", n_layers=2, n_q_heads=8, n_kv_heads=4, head_dim=128, seq_lens=(3000, 700, 5121),
+        n_window=16, n_lookahead=8, pool_k=7, c_max=256, dtype="bf16", sm_scale=1.0 / math.sqrt(128.0),
+        n_planted=16, seed=11)
+    t = workloads.generate(w)
+    q, k, v = (t[x].cuda() for x in ("q", "k", "v"))
+    p = make_params(S, w)
+    L, H, KT, d = w.n_layers, w.n_kv_heads, S.total_keep(p), w.head_dim
+    ws = torch.empty(S.ada_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    q64, k64, v64 = (workloads.to_float64(t[x]) for x in ("q", "k", "v"))
+    for c_floor in (51, 256):
+        idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+        head_off = torch.full((L, len(w.seq_lens), H + 1), -1, dtype=torch.int32, device="cuda")
+        k_out = torch.zeros((L, H * KT, d), dtype=torch.bfloat16, device="cuda")
+        v_out = torch.zeros_like(k_out)
+        S.speckv_compress_ada(p, c_floor, q, k, v, idx, head_off, k_out, v_out, ws)
+        torch.cuda.synchronize()
+        idx_h, off_h = idx.cpu().numpy(), head_off.cpu().numpy()
+        ko, vo = k_out.cpu().float().numpy(), v_out.cpu().float().numpy()
+        moved = 0
+        for layer in range(L):
+            for s, n in enumerate(w.seq_lens):
+                a, b = w.cu_seqlens[s], w.cu_seqlens[s + 1]
+                ref = orc.speckv_layer_ada(q64[layer, s], k64[layer, a:b], v64[layer, a:b], w.n_window,
+                                           w.pool_k, w.c_max, c_floor, w.sm_scale)
+                got_off = off_h[layer, s]
+                got = ada_block(w, idx_h, layer, s, w.c_max)
+                # structure: every head ascending, window last, floor respected, layer total fixed
+                assert got_off[0] == 0 and got_off[-1] == H * (min(w.c_max, n - w.n_window) + w.n_window)
+                for g in range(H):
+                    rows = got[got_off[g]:got_off[g + 1]]
+                    assert (np.diff(rows) > 0).all() and rows[-w.n_window:].tolist() == list(range(n - w.n_window, n))
+                    assert len(rows) - w.n_window >= min(c_floor, w.c_max, n - w.n_window)
+                # the sets match the oracle wherever its own score gaps exceed the tolerance
+                if got_off.tolist() == ref["head_off"].tolist() and got.tolist() == np.concatenate(ref["idx"]).tolist():
+                    pass
+                else:
+                    # scores near the layer threshold may fall either way: compare the kept pooled mass
+                    pooled = ref["pooled"]
+                    mass = lambda off, ix: sum(pooled[g][ix[off[g]:off[g + 1]][:-w.n_window]].sum() for g in range(H))
+                    want_mass = mass(ref["head_off"], np.concatenate(ref["idx"]))
+                    assert abs(mass(got_off, got) - want_mass) <= REL_TOL * want_mass
+                    moved += 1
+                # gathered rows are bit copies of the rows the returned indices name
+                kb = ada_block(w, ko, layer, s, w.c_max)
+                vb = ada_block(w, vo, layer, s, w.c_max)
+                for g in range(H):
+                    rows = got[got_off[g]:got_off[g + 1]]
+                    assert np.array_equal(kb[got_off[g]:got_off[g + 1]], k64[layer, a:b][rows, g, :])
+                    assert np.array_equal(vb[got_off[g]:got_off[g + 1]], v64[layer, a:b][rows, g, :])
+        assert moved <= 1, "index sets differ from the oracle in %d blocks" % moved
+        if c_floor == 256:
+            idx_u = torch.empty_like(idx); k_u = torch.empty_like(k_out); v_u = torch.empty_like(v_out)
+            S.speckv_compress(p, q, k, v, idx_u, k_u, v_u, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(idx_u, idx) and torch.equal(k_u, k_out) and torch.equal(v_u, v_out)
