@@ -687,3 +687,71 @@ def test_compress_ada_full_path(S):
             S.speckv_compress(p, q, k, v, idx_u, k_u, v_u, ws)
             torch.cuda.synchronize()
             assert torch.equal(idx_u, idx) and torch.equal(k_u, k_out) and torch.equal(v_u, v_out)
+
+
+def test_cascade_prompt_compression_then_cache_compression(S):
+    """SpecKV-PC (Sec. "SpecKV-PC: Cascaded Compression"): Alg. 2 shortens the prompt from the draft
+    model's attention, the target model is prefilled on the kept tokens, Alg. 1 compresses that
+    cache.  The target prefill is outside this library; its K/V of the kept tokens are stood in
+    for by the rows of a synthetic target tensor at the kept positions (a torch gather here, the
+    same gather in numpy for the oracle).  Both stages run on one stream, the second sized by the
+    count the first returns."""
+    n_in, l_skip, n_neighbor, keep_tokens = 6000, 2, 9, 1500
+    base = workloads.specpc_draft(n_in=n_in, n_layers=5, name="pc_draft")
+    wd = workloads.SpecKVWorkload(**{**base.__dict__, "n_lookahead": 4, "pool_k": 5, "c_max": keep_tokens})
+    td = workloads.generate(wd)
+    ids = workloads.generate_token_ids(wd)
+    wt = workloads.llama8b_layer(n_in=n_in, c_max=200, n_layers=2, seed=23, name="pc_target")
+    tt = workloads.generate(wt)
+
+    # oracle: stage 1, gather, stage 2
+    ref1 = orc.specpc_compress_prompt(workloads.to_float64(td["q"][:, 0]), workloads.to_float64(td["k"]),
+                                      ids.numpy(), wd.n_window, wd.pool_k, n_neighbor, keep_tokens, l_skip,
+                                      wd.sm_scale)
+    kept = ref1["idx"]
+    assert kept[-wt.n_window:].tolist() == list(range(n_in - wt.n_window, n_in))   # target's window rows survive
+    q64, k64, v64 = (workloads.to_float64(tt[x]) for x in ("q", "k", "v"))
+    ref2 = [orc.speckv_layer(q64[layer, 0], k64[layer][kept], v64[layer][kept], wt.n_window, wt.pool_k,
+                             wt.c_max, wt.sm_scale) for layer in range(wt.n_layers)]
+
+    # library: stage 1
+    p1 = make_params(S, wd)
+    ws1 = torch.empty(S.specpc_compress_workspace_bytes(p1, l_skip), dtype=torch.uint8, device="cuda")
+    cap = keep_tokens + wd.n_window
+    idx_out = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    ids_out = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    S.specpc_compress_prompt(p1, l_skip, n_neighbor, td["q"].cuda(), td["k"].cuda(), ids.cuda(), idx_out,
+                             ids_out, count, ws1)
+    n2 = int(count.item())                                            # the one host round trip of the cascade
+    got_kept = idx_out[:n2].cpu().numpy().astype(np.int64)
+    assert_indices_valid(got_kept, ref1["pooled"], n_in, wd.n_window, keep_tokens, "cascade stage 1")
+    assert np.array_equal(got_kept, kept), "stage 1 differs inside its tolerance band: pick another seed"
+    np.testing.assert_array_equal(ids_out[:n2].cpu().numpy(), ids.numpy()[kept])
+
+    # stand-in for the target prefill on the kept tokens
+    k2 = tt["k"].cuda().index_select(1, idx_out[:n2].long()).contiguous()
+    v2 = tt["v"].cuda().index_select(1, idx_out[:n2].long()).contiguous()
+    q2 = tt["q"].cuda()
+
+    # library: stage 2 on the shortened prompt
+    w2 = workloads.SpecKVWorkload(**{**wt.__dict__, "seq_lens": (n2,)})
+    p2 = make_params(S, w2)
+    KT = S.total_keep(p2)
+    H, d, L = wt.n_kv_heads, wt.head_dim, wt.n_layers
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    k_out = torch.empty((L, H * KT, d), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
+    S.speckv_compress(p2, q2, k2, v2, idx, k_out, v_out, alloc_ws(S, p2))
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy().reshape(L, H, KT)
+    ko = k_out.cpu().float().numpy().reshape(L, H, KT, d)
+    vo = v_out.cpu().float().numpy().reshape(L, H, KT, d)
+    for layer in range(L):
+        for g in range(H):
+            assert_indices_valid(idx_h[layer, g], ref2[layer]["pooled"][g], n2, wt.n_window, wt.c_max,
+                                 "cascade stage 2 l%d g%d" % (layer, g))
+            # rows of the final cache are rows of the ORIGINAL prompt: kept[idx] names them
+            orig = kept[idx_h[layer, g]]
+            assert np.array_equal(ko[layer, g], k64[layer][orig, g, :])
+            assert np.array_equal(vo[layer, g], v64[layer][orig, g, :])
