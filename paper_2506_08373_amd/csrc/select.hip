@@ -104,16 +104,26 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_all_kernel(
 // ----------------------------------------------------------------------------------
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelPerThread = 4;
+constexpr int kSelVec = 4;         // 128-bit vectors a thread ranks per tile of the emission pass
 constexpr int kHistCopies = 8;
-constexpr int kHistUnroll = 8;     // independent loads in flight per thread in the histogram passes
+constexpr int kHistUnroll = 4;     // independent 128-bit loads in flight per thread in the histogram passes
 
-// Order-preserving map float -> uint32 (larger float, larger key); -0 counts as +0.
-__device__ inline uint32_t order_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if (u == 0x80000000u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+// Ordered key of a float (larger float, larger key): with u its bits and -0 taken as +0,
+// key = u | 0x80000000 for a positive number and ~u for a negative one.  `prefix` values below
+// are leading bits of such keys.
+// The histogram passes work on the raw float bits (fewer operations per element than the ordered
+// key); only the bin index is translated when the bins are read in descending order.
+// Ordered digit D of level `pass` (0, 1, 2) -> digit of the raw bits; `neg`: the number is negative.
+__device__ __forceinline__ int raw_digit(int D, int pass, int nb, bool neg) {
+  if (pass == 0) return D >= 1024 ? D - 1024 : 2047 - D;
+  return neg ? nb - 1 - D : D;
 }
+// Raw float bits (under `mask`) of the numbers whose ordered key starts with `prefix`.
+__device__ __forceinline__ uint32_t raw_prefix_of(uint32_t prefix, uint32_t mask) {
+  return (prefix & 0x80000000u) ? (prefix ^ 0x80000000u) : (~prefix & mask);
+}
+// Raw bits of x with -0 turned into +0 (the two compare equal and must share a bin).
+__device__ __forceinline__ uint32_t raw_bits(float x) { return __float_as_uint(x + 0.0f); }
 
 struct SelShared {
   uint32_t hist[kHistCopies * 2048];   // one copy per lane residue: spreads atomics that hit one bin
@@ -144,39 +154,74 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *w
   return before + inc - v;
 }
 
+// A row split for 128-bit access: `lead` scalars up to the first 16-byte boundary, nv float4
+// vectors, then the scalars from tail0 to the end.
+struct RowSplit { int lead, nv, tail0; };
+__device__ __forceinline__ RowSplit split_row(const float *x, int m) {
+  RowSplit rs;
+  rs.lead = min((int)((4u - ((uint32_t)(reinterpret_cast<uintptr_t>(x) >> 2) & 3u)) & 3u), m);
+  rs.nv = (m - rs.lead) >> 2;
+  rs.tail0 = rs.lead + 4 * rs.nv;
+  return rs;
+}
+
+// Histogram of one radix digit of the entries of x[0..m) whose ordered key starts with `prefix`
+// (bits under `mask`), into the kHistCopies copies of sh.hist (cleared first), indexed by the digit
+// of the RAW bits (see raw_digit).  The loads are unconditional (index clamped) so that kHistUnroll
+// vectors per thread are in flight.
+__device__ __forceinline__ void histogram_pass(const float *__restrict__ x, int m, RowSplit rs,
+                                               uint32_t prefix, uint32_t mask, int shift, int nb,
+                                               SelShared &sh) {
+  const int tid = threadIdx.x;
+  for (int b = tid; b < kHistCopies * 2048; b += kSelThreads) sh.hist[b] = 0;
+  __syncthreads();
+  uint32_t *h = sh.hist + (tid % kHistCopies) * 2048;
+  const uint32_t rawp = raw_prefix_of(prefix, mask);
+  const float4 *xv = reinterpret_cast<const float4 *>(x + rs.lead);
+  for (int v0 = 0; v0 < rs.nv; v0 += kSelThreads * kHistUnroll) {
+    float4 val[kHistUnroll];
+#pragma unroll
+    for (int u = 0; u < kHistUnroll; ++u) val[u] = xv[min(v0 + u * kSelThreads + tid, rs.nv - 1)];
+#pragma unroll
+    for (int u = 0; u < kHistUnroll; ++u) {
+      const bool ok = v0 + u * kSelThreads + tid < rs.nv;
+      const float e4[4] = {val[u].x, val[u].y, val[u].z, val[u].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t u = raw_bits(e4[c]);
+        if (ok && ((u ^ rawp) & mask) == 0) atomicAdd(&h[(u >> shift) & (nb - 1)], 1u);
+      }
+    }
+  }
+  if (tid < rs.lead + (m - rs.tail0)) {
+    const uint32_t u = raw_bits(x[tid < rs.lead ? tid : rs.tail0 + (tid - rs.lead)]);
+    if (((u ^ rawp) & mask) == 0) atomicAdd(&h[(u >> shift) & (nb - 1)], 1u);
+  }
+  __syncthreads();
+}
+
 // Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
 // equal values taken from the low-index end.
 __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int m, int count,
                                int32_t *__restrict__ out, SelShared &sh) {
   const int tid = threadIdx.x;
+  const RowSplit rs = split_row(x, m);
   uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
 #pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : pass == 1 ? 10 : 0;       // digits of 11, 11 and 10 bits
     const int nb = pass == 2 ? 1024 : 2048;
-    for (int b = tid; b < kHistCopies * 2048; b += kSelThreads) sh.hist[b] = 0;
-    __syncthreads();
-    // the loads are unconditional (index clamped) so that kHistUnroll of them are in flight
-    for (int j0 = 0; j0 < m; j0 += kSelThreads * kHistUnroll) {
-      float val[kHistUnroll];
-#pragma unroll
-      for (int u = 0; u < kHistUnroll; ++u) val[u] = x[min(j0 + u * kSelThreads + tid, m - 1)];
-#pragma unroll
-      for (int u = 0; u < kHistUnroll; ++u) {
-        const uint32_t key = order_key(val[u]);
-        if (j0 + u * kSelThreads + tid < m && (key & mask) == prefix)
-          atomicAdd(&sh.hist[(tid % kHistCopies) * 2048 + ((key >> shift) & (nb - 1))], 1u);
-      }
-    }
-    __syncthreads();
+    histogram_pass(x, m, rs, prefix, mask, shift, nb, sh);
     // thread t owns the bins nb-1-2t and nb-2-2t: scanning threads in order walks the
     // bins from the largest digit down.
     const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+    const bool neg = (prefix & 0x80000000u) == 0;
+    const int r0 = raw_digit(b0, pass, nb, neg), r1 = raw_digit(b1, pass, nb, neg);
     uint32_t c0 = 0, c1 = 0;
 #pragma unroll
     for (int cp = 0; cp < kHistCopies; ++cp) {
-      if (b0 >= 0) c0 += sh.hist[cp * 2048 + b0];
-      if (b1 >= 0) c1 += sh.hist[cp * 2048 + b1];
+      if (b0 >= 0) c0 += sh.hist[cp * 2048 + r0];
+      if (b1 >= 0) c1 += sh.hist[cp * 2048 + r1];
     }
     uint32_t total;
     const uint32_t above = block_exclusive_scan(c0 + c1, sh.wave_tot[0], &total);
@@ -195,40 +240,71 @@ __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int 
   }
   // prefix is now the key of the count-th largest value; `remaining` of the entries equal
   // to it are taken, from the low-index end.
-  const uint32_t thr = prefix, need_eq = remaining;
+  // (compared as floats: the same order as the keys, with -0 equal to +0)
+  const float thr = __uint_as_float(raw_prefix_of(prefix, 0xffffffffu));
+  const uint32_t need_eq = remaining;
   uint32_t run_gt = 0, run_eq = 0;
-  int buf = 0;
-  // the values of the next tile are requested before the current tile is ranked
-  float val[kSelPerThread], nxt[kSelPerThread];
+  // the scalars before the first vector: every thread tracks the counts, thread 0 writes
+  for (int j = 0; j < rs.lead; ++j) {
+    const float xj = x[j];
+    const bool is_gt = xj > thr, is_eq = xj == thr;
+    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = j;
+    run_gt += is_gt;
+    run_eq += is_eq;
+  }
+  if (rs.nv > 0) {
+    // a thread ranks kSelVec adjacent vectors per tile; the values of the next tile are
+    // requested before the current tile is ranked
+    const float4 *xv = reinterpret_cast<const float4 *>(x + rs.lead);
+    constexpr int kTileVec = kSelThreads * kSelVec;
+    float4 val[kSelVec], nxt[kSelVec];
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e) val[e] = x[min(tid * kSelPerThread + e, m - 1)];
-  for (int j0 = 0; j0 < m; j0 += kSelThreads * kSelPerThread, buf ^= 1) {
-    const int jb = j0 + tid * kSelPerThread;
+    for (int e = 0; e < kSelVec; ++e) val[e] = xv[min(tid * kSelVec + e, rs.nv - 1)];
+    int buf = 0;
+    for (int v0 = 0; v0 < rs.nv; v0 += kTileVec, buf ^= 1) {
+      const int vb = v0 + tid * kSelVec;
 #pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) nxt[e] = x[min(jb + kSelThreads * kSelPerThread + e, m - 1)];
-    uint32_t gt_bits = 0, eq_bits = 0, cg = 0, ce = 0;
+      for (int e = 0; e < kSelVec; ++e) nxt[e] = xv[min(vb + kTileVec + e, rs.nv - 1)];
+      uint32_t gt_bits = 0, eq_bits = 0;
 #pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) {
-      const uint32_t key = order_key(val[e]);
-      if (jb + e < m && key > thr) { gt_bits |= 1u << e; ++cg; }
-      if (jb + e < m && key == thr) { eq_bits |= 1u << e; ++ce; }
+      for (int e = 0; e < kSelVec; ++e) {
+        const float e4[4] = {val[e].x, val[e].y, val[e].z, val[e].w};
+        uint32_t g4 = 0, q4 = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          g4 |= e4[c] > thr ? 1u << c : 0u;
+          q4 |= e4[c] == thr ? 1u << c : 0u;
+        }
+        if (vb + e < rs.nv) { gt_bits |= g4 << (4 * e); eq_bits |= q4 << (4 * e); }
+      }
+      const uint32_t cg = __popc(gt_bits), ce = __popc(eq_bits);
+      // one scan for both counts: gt in the low 16 bits, eq in the high 16 bits
+      // (a tile holds at most 16384 entries, so neither field can overflow)
+      uint32_t total;
+      const uint32_t before = block_exclusive_scan(cg | (ce << 16), sh.wave_tot[buf], &total);
+      uint32_t gt_before = run_gt + (before & 0xffffu), eq_before = run_eq + (before >> 16);
+      if ((gt_bits | eq_bits) != 0) {
+#pragma unroll
+        for (int b = 0; b < 4 * kSelVec; ++b) {
+          const bool is_gt = (gt_bits >> b) & 1u, is_eq = (eq_bits >> b) & 1u;
+          if (is_gt || (is_eq && eq_before < need_eq))
+            out[gt_before + min(eq_before, need_eq)] = rs.lead + 4 * vb + b;
+          gt_before += is_gt;
+          eq_before += is_eq;
+        }
+      }
+      run_gt += total & 0xffffu;
+      run_eq += total >> 16;
+#pragma unroll
+      for (int e = 0; e < kSelVec; ++e) val[e] = nxt[e];
     }
-    // one scan for both counts: gt in the low 16 bits, eq in the high 16 bits
-    // (a tile holds at most 4096 entries, so neither field can overflow)
-    uint32_t total;
-    const uint32_t before = block_exclusive_scan(cg | (ce << 16), sh.wave_tot[buf], &total);
-    uint32_t gt_before = run_gt + (before & 0xffffu), eq_before = run_eq + (before >> 16);
-#pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) {
-      const bool is_gt = (gt_bits >> e) & 1u, is_eq = (eq_bits >> e) & 1u;
-      if (is_gt || (is_eq && eq_before < need_eq)) out[gt_before + min(eq_before, need_eq)] = jb + e;
-      gt_before += is_gt;
-      eq_before += is_eq;
-    }
-    run_gt += total & 0xffffu;
-    run_eq += total >> 16;
-#pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) val[e] = nxt[e];
+  }
+  for (int j = rs.tail0; j < m; ++j) {
+    const float xj = x[j];
+    const bool is_gt = xj > thr, is_eq = xj == thr;
+    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = j;
+    run_gt += is_gt;
+    run_eq += is_eq;
   }
 }
 
@@ -286,25 +362,16 @@ __global__ __launch_bounds__(kSelThreads) void ada_hist_kernel(Dims d, SeqTab t,
   const int shift = ada_shift(level), nb = ada_bins(level);
   const uint32_t mask = level == 0 ? 0u : level == 1 ? 0xffe00000u : 0xfffffc00u;
   const uint32_t prefix = level == 0 ? 0u : state[(int64_t)ls * (2 + 2 * d.Hkv)];
-  for (int b = tid; b < kHistCopies * 2048; b += kSelThreads) sh.hist[b] = 0;
-  __syncthreads();
-  for (int j0 = 0; j0 < m; j0 += kSelThreads * kHistUnroll) {
-    float val[kHistUnroll];
-#pragma unroll
-    for (int u = 0; u < kHistUnroll; ++u) val[u] = x[min(j0 + u * kSelThreads + tid, m - 1)];
-#pragma unroll
-    for (int u = 0; u < kHistUnroll; ++u) {
-      const uint32_t key = order_key(val[u]);
-      if (j0 + u * kSelThreads + tid < m && (key & mask) == prefix)
-        atomicAdd(&sh.hist[(tid % kHistCopies) * 2048 + ((key >> shift) & (nb - 1))], 1u);
-    }
-  }
-  __syncthreads();
+  histogram_pass(x, max(m, 0), split_row(x, max(m, 0)), prefix, mask, shift, nb, sh);
   uint32_t *out = hist + (int64_t)unit * 2048;
-  for (int b = tid; b < 2048; b += kSelThreads) {
+  const bool neg = (prefix & 0x80000000u) == 0;
+  for (int b = tid; b < 2048; b += kSelThreads) {       // b: ordered digit
     uint32_t c = 0;
+    if (b < nb) {
+      const int r = raw_digit(b, level, nb, neg);
 #pragma unroll
-    for (int cp = 0; cp < kHistCopies; ++cp) c += sh.hist[cp * 2048 + b];
+      for (int cp = 0; cp < kHistCopies; ++cp) c += sh.hist[cp * 2048 + r];
+    }
     out[b] = c;
   }
 }

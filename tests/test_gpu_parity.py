@@ -755,3 +755,32 @@ def test_cascade_prompt_compression_then_cache_compression(S):
             orig = kept[idx_h[layer, g]]
             assert np.array_equal(ko[layer, g], k64[layer][orig, g, :])
             assert np.array_equal(vo[layer, g], v64[layer][orig, g, :])
+
+
+def test_select_signed_zeros_denormals_and_negative_rows(S):
+    """-0 and +0 tie (smaller index first), denormal scores keep their order, rows that are all
+    negative or mixed select from the right end of the order."""
+    n_window, H = 2, 6
+    m = 5003
+    n = m + n_window
+    rng = np.random.default_rng(5)
+    rows = np.zeros((H, n), dtype=np.float32)
+    rows[0, :m] = np.where(rng.random(m) < 0.5, np.float32(0.0), np.float32(-0.0))          # only zeros
+    rows[1, :m] = (rng.integers(-3, 4, size=m) * np.float32(1e-42)).astype(np.float32)       # denormals, zeros
+    rows[1, ::7] = np.float32(-0.0)
+    rows[2, :m] = -np.abs(rng.standard_normal(m)).astype(np.float32) - 1                     # all negative
+    rows[3, :m] = rng.standard_normal(m).astype(np.float32) * np.float32(1e-30)              # mixed signs, tiny
+    rows[4, :m] = rng.integers(-2, 3, size=m).astype(np.float32)                             # few levels around 0
+    rows[5, :m] = np.float32(3.0e38) * rng.choice([-1, 1], size=m).astype(np.float32)        # extremes
+    for c_max in (1, 700, 2600, m):
+        w = workloads.SpecKVWorkload(
+            name="zeros", n_layers=1, n_q_heads=H, n_kv_heads=H, head_dim=64, seq_lens=(n,),
+            n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+        p = make_params(S, w)
+        idx = torch.full((1, H * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
+        S.speckv_select(p, torch.from_numpy(rows.reshape(1, -1)).cuda(), idx)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy().reshape(H, -1)
+        for g in range(H):
+            want = orc.keep_indices(rows[g, :m].astype(np.float64), n, n_window, c_max)
+            assert got[g].tolist() == want.tolist(), (c_max, g)
