@@ -7,7 +7,11 @@
 //    smaller index, ascending, then the window m..n_in-1 (Alg. 1 "Select KVs").
 //    MSD radix select on order-preserving 32-bit keys (11 + 11 + 10 bits, LDS
 //    histograms), then an ordered compaction that ranks candidates with wavefront
-//    prefix sums.  One workgroup per row; every step is deterministic.
+//    prefix sums.  One workgroup per row; every step is deterministic.  A workgroup is
+//    bound by its vector ALU, so the per-element work is kept minimal: 128-bit loads,
+//    digits taken from the raw float bits, float compares against the threshold.
+//  * shared layer budget: per-head counts from one layer-wide threshold (histogram and
+//    decision kernels per digit), then the same row select with each head's own count.
 //  * expand: widens selected tokens to +-n_neighbor, unites them with the window and
 //    emits the sorted set with the token ids gathered (Sec. 4.2 prompt compression).
 #include "speckv_internal.h"
