@@ -784,3 +784,26 @@ def test_select_signed_zeros_denormals_and_negative_rows(S):
         for g in range(H):
             want = orc.keep_indices(rows[g, :m].astype(np.float64), n, n_window, c_max)
             assert got[g].tolist() == want.tolist(), (c_max, g)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_configurations(S, seed):
+    """Seeded random shapes: group size, rows per head, head dimension, number type, ragged lengths,
+    window, lookahead, pooling width, budget, reduction and pooling options, all drawn together so
+    that combinations no hand-written case names are exercised too."""
+    rng = np.random.default_rng(7000 + seed)
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    d = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    n_window = int(rng.choice([0, 1, 7, 16, 33, 64]))
+    n_lookahead = int(rng.choice([0, 1, 5, 32, 70])) if n_window > 0 else int(rng.choice([1, 5, 32, 70]))
+    n_seqs = int(rng.choice([1, 2, 4]))
+    lens = tuple(int(x) for x in rng.integers(max(1, n_window), 2600, size=n_seqs))
+    w = workloads.SpecKVWorkload(
+        name="rand%d" % seed, n_layers=int(rng.choice([1, 2])), n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d,
+        seq_lens=lens, n_window=n_window, n_lookahead=n_lookahead, pool_k=int(rng.choice([1, 3, 7, 13])),
+        c_max=int(rng.choice([0, 1, 50, 400, 5000])), dtype=dtype, sm_scale=float(1.0 / math.sqrt(d)),
+        n_planted=int(rng.choice([0, 3])) if min(lens) - n_window > 8 else 0,
+        channel_scale=(0.5, 4.0) if rng.random() < 0.5 else None, seed=300 + seed)
+    check_full_path(S, w, reduce=str(rng.choice(["sum", "sum", "max"])), pool=str(rng.choice(["max", "max", "avg"])))
