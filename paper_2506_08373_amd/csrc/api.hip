@@ -10,7 +10,9 @@ namespace speckv {
 namespace {
 
 constexpr int64_t kTokenLimit = (int64_t)1 << 30;   // total tokens per call
-constexpr int kTargetWorkgroups = 1024;             // scoring grid: about 4 workgroups per CU
+constexpr int kTargetWorkgroups = 1024;             // scoring grid: at least about 4 workgroups per CU
+constexpr int kChunkFloor = 8192;                   // chunks are not shortened below this to balance the grid
+constexpr int kWorkgroupCost = 190;                 // fixed cost of a scoring workgroup, in keys (measured)
 constexpr int kCUs = 256;                           // compute units of an MI355X
 constexpr int kChunkAlign = 128;                    // chunk = whole LDS key tiles
 
@@ -102,11 +104,36 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
     t.tail0[s] = visible_to_all / kt * kt;
     fast_keys += t.tail0[s];
   }
-  // Chunk length: about four workgroups per CU for large problems; small problems get longer
-  // chunks (up to 2048 keys) as long as one workgroup per CU remains, because every workgroup
-  // pays for loading its Q fragments and row normalisers.
+  // Chunk length.  A workgroup pays for loading its Q fragments and row normalisers (about
+  // kWorkgroupCost keys' worth of time), so chunks should not be short; but the grid runs in rounds
+  // of one workgroup per CU, so few or unequal workgroups (ragged batches) leave CUs idle at the
+  // end.  Start from about four workgroups per CU and halve the chunk while a simple model of the
+  // sweep's duration (in key-times per CU) improves; tiny problems get longer chunks (up to 2048
+  // keys) as long as one workgroup per CU remains.
   const int64_t many = (kTargetWorkgroups + units - 1) / units, few = (kCUs + units - 1) / units;
+  auto sweep_time = [&](int64_t kc_) {
+    int64_t chunks = 0;
+    bool equal = true;
+    for (int s = 0; s < d.S; ++s) {
+      chunks += (t.tail0[s] + kc_ - 1) / kc_;
+      if (t.tail0[s] % kc_ != 0) equal = false;
+    }
+    const double n_wg = (double)chunks * (double)units;
+    const double rounds = std::ceil(n_wg / kCUs) * (double)(kc_ + kWorkgroupCost);
+    if (equal) return rounds;                                   // identical workgroups: whole rounds
+    const double spread = ((double)fast_keys * (double)units + n_wg * kWorkgroupCost) / kCUs +
+                          0.75 * (double)(kc_ + kWorkgroupCost);  // even spread plus a ragged last round
+    return rounds < spread ? rounds : spread;
+  };
   int64_t kc = align_up((fast_keys + many - 1) / many, kChunkAlign);
+  if (kc > kChunkFloor) {
+    double best = sweep_time(kc);
+    for (int64_t cand = (int64_t)1 << 20; cand >= kChunkFloor; cand >>= 1) {
+      if (cand >= kc) continue;
+      const double tm = sweep_time(cand);
+      if (tm < best) { best = tm; kc = cand; }
+    }
+  }
   int64_t kc_few = align_up((fast_keys + few - 1) / few, kChunkAlign);
   if (kc_few > 16 * kChunkAlign) kc_few = 16 * kChunkAlign;
   if (kc < kc_few) kc = kc_few;

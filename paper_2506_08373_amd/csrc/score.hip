@@ -124,23 +124,31 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   const Dims &d = A.d;
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int unit = blockIdx.y;
-  const int rs = unit % A.g.RS;
-  const int g = (unit / A.g.RS) % d.Hkv;
-  const int layer = unit / (A.g.RS * d.Hkv);
-  int s, chunk, key_begin, key_end;
+  int unit, s, chunk, key_begin, key_end;
   if (MASKED) {
+    unit = blockIdx.y;
     s = blockIdx.x;
     chunk = A.g.n_fast_chunks + s;
     key_begin = A.t.tail0[s];
     key_end = A.t.cu[s + 1] - A.t.cu[s];
   } else {
-    chunk = blockIdx.x;
+    // 1-D grid.  Workgroups go to the 8 XCDs round-robin by their linear id and each XCD has its
+    // own L2, so the RS row super-blocks that sweep the SAME keys of a (layer, head) get ids 8
+    // apart: same XCD, dispatched together, and the keys come from HBM once instead of RS times.
+    const int per_group = 8 * A.g.RS;
+    const int grp = blockIdx.x / per_group, within = blockIdx.x % per_group;
+    const int item = grp * 8 + (within & 7);            // (layer, head, chunk), chunk fastest
+    if (item >= A.g.n_fast_chunks * d.L * d.Hkv) return;
+    chunk = item % A.g.n_fast_chunks;
+    unit = (item / A.g.n_fast_chunks) * A.g.RS + (within >> 3);
     s = 0;
     while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
     key_begin = (chunk - A.t.cc[s]) * A.g.KC;
     key_end = min(A.t.tail0[s], key_begin + A.g.KC);
   }
+  const int rs = unit % A.g.RS;
+  const int g = (unit / A.g.RS) % d.Hkv;
+  const int layer = unit / (A.g.RS * d.Hkv);
   const int n_s = A.t.cu[s + 1] - A.t.cu[s];
   const int m = n_s - d.w;
   const int ntiles = (key_end - key_begin + KT - 1) / KT;
@@ -567,7 +575,10 @@ hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
   const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
   hipError_t e;
   if (A.g.n_fast_chunks > 0) {
-    const dim3 grid(A.g.n_fast_chunks, units), block(NW * 64);
+    const int64_t items = (int64_t)A.g.n_fast_chunks * A.d.L * A.d.Hkv;
+    const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS;
+    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs), block(NW * 64);
     if (PASS == 1 && NW == 8) e = launch_one(score_kernel_rows<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     else e = launch_one(score_kernel_cols<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     if (e != hipSuccess) return e;
