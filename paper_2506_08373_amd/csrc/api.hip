@@ -108,7 +108,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   // kWorkgroupCost keys' worth of time), so chunks should not be short; but the grid runs in rounds
   // of one workgroup per CU, so few or unequal workgroups (ragged batches) leave CUs idle at the
   // end.  Start from about four workgroups per CU and halve the chunk while a simple model of the
-  // sweep's duration (in key-times per CU) improves; tiny problems get longer chunks (up to 2048
+  // sweep's duration (in key-times per CU) improves; tiny problems get longer chunks (up to 4096
   // keys) as long as one workgroup per CU remains.
   const int64_t many = (kTargetWorkgroups + units - 1) / units, few = (kCUs + units - 1) / units;
   auto sweep_time = [&](int64_t kc_) {
@@ -135,7 +135,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
     }
   }
   int64_t kc_few = align_up((fast_keys + few - 1) / few, kChunkAlign);
-  if (kc_few > 16 * kChunkAlign) kc_few = 16 * kChunkAlign;
+  if (kc_few > 32 * kChunkAlign) kc_few = 32 * kChunkAlign;
   if (kc < kc_few) kc = kc_few;
   if (kc < 4 * kChunkAlign) kc = 4 * kChunkAlign;
   g.KC = (int32_t)kc;
