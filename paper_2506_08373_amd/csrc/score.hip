@@ -176,6 +176,42 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   }
 #define SPECKV_ROW_VALID(rb_, r32_) (blk_head[rb_] >= 0 && blk_i0[rb_] + (r32_) < d.R)
 
+  // ---- K tile staging: each wave issues SEG_PER_WAVE wave-wide 128-bit loads that land in LDS
+  // at lds_base + lane*16; the lane picks the global chunk that belongs in its (row, slot).
+  const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
+  const int64_t tokb = d.kv_st * ELT;
+  const int st_row = (lane * 16) / ROWB, st_slot = ((lane * 16) % ROWB) / 16;
+  // unmasked sweep: the lane's byte offset inside a tile never changes, only the (uniform) tile
+  // base moves, so the loads use a scalar base plus a 32-bit lane offset
+  uint32_t loff[SEG_PER_WAVE];
+#pragma unroll
+  for (int it = 0; it < SEG_PER_WAVE; ++it) {
+    const int r_ = (it * NW + wv) * RPS + st_row;
+    loff[it] = (uint32_t)r_ * (uint32_t)tokb + (uint32_t)((st_slot ^ TL::swizzle(r_)) * 16);
+  }
+#define SPECKV_LOAD_TILE(tile_, buf_)                                                         \
+  {                                                                                           \
+    const int k0_ = key_begin + (tile_) * KT;                                                 \
+    const char *tbase_ = kbase + (int64_t)k0_ * tokb;                                         \
+    _Pragma("unroll") for (int it = 0; it < SEG_PER_WAVE; ++it) {                             \
+      const int seg_ = it * NW + wv;                                                          \
+      const char *src_;                                                                       \
+      if (MASKED) {                                                                           \
+        const int r_ = seg_ * RPS + st_row;                                                   \
+        /* rows past the end of the sequence re-read its last key; they are masked later */   \
+        src_ = kbase + (int64_t)min(k0_ + r_, n_s - 1) * tokb + (st_slot ^ TL::swizzle(r_)) * 16; \
+      } else {                                                                                \
+        src_ = tbase_ + loff[it];                                                             \
+      }                                                                                       \
+      __builtin_amdgcn_global_load_lds(                                                       \
+          (const __attribute__((address_space(1))) void *)src_,                               \
+          (__attribute__((address_space(3))) void *)(kbuf + (buf_) * TILE_BYTES + seg_ * 1024), 16, 0, 0); \
+    }                                                                                         \
+  }
+  // the first tile is requested before anything else is loaded, so that its latency overlaps
+  // with the Q fragment and row normaliser loads below
+  if (ntiles > 0) SPECKV_LOAD_TILE(0, 0)
+
   // ---- Q fragments of this wave's row blocks, resident for the whole sweep
   u32x4 qf[MB][NCS];
 #pragma unroll
@@ -231,38 +267,6 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     }
   }
 
-  // ---- K tile staging: each wave issues SEG_PER_WAVE wave-wide 128-bit loads that land in LDS
-  // at lds_base + lane*16; the lane picks the global chunk that belongs in its (row, slot).
-  const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * ELT;
-  const int64_t tokb = d.kv_st * ELT;
-  const int st_row = (lane * 16) / ROWB, st_slot = ((lane * 16) % ROWB) / 16;
-  // unmasked sweep: the lane's byte offset inside a tile never changes, only the (uniform) tile
-  // base moves, so the loads use a scalar base plus a 32-bit lane offset
-  uint32_t loff[SEG_PER_WAVE];
-#pragma unroll
-  for (int it = 0; it < SEG_PER_WAVE; ++it) {
-    const int r_ = (it * NW + wv) * RPS + st_row;
-    loff[it] = (uint32_t)r_ * (uint32_t)tokb + (uint32_t)((st_slot ^ TL::swizzle(r_)) * 16);
-  }
-#define SPECKV_LOAD_TILE(tile_, buf_)                                                         \
-  {                                                                                           \
-    const int k0_ = key_begin + (tile_) * KT;                                                 \
-    const char *tbase_ = kbase + (int64_t)k0_ * tokb;                                         \
-    _Pragma("unroll") for (int it = 0; it < SEG_PER_WAVE; ++it) {                             \
-      const int seg_ = it * NW + wv;                                                          \
-      const char *src_;                                                                       \
-      if (MASKED) {                                                                           \
-        const int r_ = seg_ * RPS + st_row;                                                   \
-        /* rows past the end of the sequence re-read its last key; they are masked later */   \
-        src_ = kbase + (int64_t)min(k0_ + r_, n_s - 1) * tokb + (st_slot ^ TL::swizzle(r_)) * 16; \
-      } else {                                                                                \
-        src_ = tbase_ + loff[it];                                                             \
-      }                                                                                       \
-      __builtin_amdgcn_global_load_lds(                                                       \
-          (const __attribute__((address_space(1))) void *)src_,                               \
-          (__attribute__((address_space(3))) void *)(kbuf + (buf_) * TILE_BYTES + seg_ * 1024), 16, 0, 0); \
-    }                                                                                         \
-  }
   // per-lane LDS offsets of the fragment chunks of key row l32 (same for every 32-key block)
   uint32_t foff[NCS];
 #pragma unroll
@@ -301,10 +305,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     }                                                                                        \
   }
 
-  if (ntiles > 0) {
-    SPECKV_LOAD_TILE(0, 0)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   // one tile of the sweep; the LDS buffer index is a compile-time constant so that every LDS
