@@ -807,3 +807,22 @@ def test_random_configurations(S, seed):
         n_planted=int(rng.choice([0, 3])) if min(lens) - n_window > 8 else 0,
         channel_scale=(0.5, 4.0) if rng.random() < 0.5 else None, seed=300 + seed)
     check_full_path(S, w, reduce=str(rng.choice(["sum", "sum", "max"])), pool=str(rng.choice(["max", "max", "avg"])))
+
+
+def test_select_on_a_three_million_key_row(S):
+    """A row far longer than any benchmark row (many emission tiles, counts above 16 bits)."""
+    n, n_window, c_max = 3_000_001, 5, 200_000
+    rng = np.random.default_rng(9)
+    rows = rng.standard_normal((2, n)).astype(np.float32)
+    rows[1] = np.round(rows[1] * 50) / 50                     # heavy ties
+    w = workloads.SpecKVWorkload(
+        name="long_row", n_layers=1, n_q_heads=2, n_kv_heads=2, head_dim=64, seq_lens=(n,),
+        n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+    p = make_params(S, w)
+    idx = torch.full((1, 2 * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
+    S.speckv_select(p, torch.from_numpy(rows.reshape(1, -1)).cuda(), idx)
+    torch.cuda.synchronize()
+    got = idx.cpu().numpy().reshape(2, -1)
+    for g in range(2):
+        want = orc.keep_indices(rows[g, :n - n_window].astype(np.float64), n, n_window, c_max)
+        assert np.array_equal(got[g], want), g
