@@ -223,3 +223,13 @@ def test_shared_layer_budget_128k(S):
         must = np.nonzero(pooled[g] > min(tau, floor_tau) + band)[0]
         never = np.nonzero(pooled[g] < min(tau, floor_tau) - band)[0]
         assert np.isin(must, sel).all() and not np.isin(never, sel).any()
+
+
+def test_one_million_token_prompt(S):
+    """Eight times the longest benchmark prompt, ragged end: 64-bit offsets, many chunks, and the
+    fp32 column sums of 2^20 keys against the float64 oracle on one head."""
+    base = workloads.llama8b_layer(n_in=(1 << 20) + 77, c_max=4096, n_layers=1, seed=31, name="one_million")
+    w = workloads.SpecKVWorkload(**{**base.__dict__, "n_q_heads": 4, "n_kv_heads": 2})
+    data, p, idx, k_out, v_out, pooled = run_workload(S, w)
+    check_structure_everywhere(w, data, idx, k_out, v_out)
+    check_sampled_heads(w, data, idx, pooled, [(0, 0, 1)])
