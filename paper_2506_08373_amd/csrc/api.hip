@@ -155,7 +155,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   pl->off_sel = take(one_row_per_call ? (size_t)(top_k > 0 ? top_k : 0) * sizeof(int32_t) : 0);
   pl->total = off;
   pl->off_ada_hist = take((size_t)d.L * d.S * d.Hkv * 2048 * sizeof(uint32_t));
-  pl->off_ada_state = take((size_t)d.L * d.S * (2 + 2 * (size_t)d.Hkv) * sizeof(uint32_t));
+  pl->off_ada_state = take((size_t)d.L * d.S * (2 + 3 * (size_t)d.Hkv) * sizeof(uint32_t));
   pl->total_ada = off;
   return SPECKV_OK;
 }

@@ -204,12 +204,11 @@ __device__ __forceinline__ void histogram_pass(const float *__restrict__ x, int 
   __syncthreads();
 }
 
-// Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
-// equal values taken from the low-index end.
-__device__ __forceinline__ void select_top_row(const float *__restrict__ x, int m, int count,
-                               int32_t *__restrict__ out, SelShared &sh) {
+// Ordered key of the count-th largest entry of x[0..m) (1 <= count <= m) and how many of the
+// entries equal to it belong to the `count` largest.
+__device__ __forceinline__ void radix_threshold(const float *__restrict__ x, int m, RowSplit rs, int count,
+                                                SelShared &sh, uint32_t *thr_key, uint32_t *need_eq_out) {
   const int tid = threadIdx.x;
-  const RowSplit rs = split_row(x, m);
   uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
 #pragma unroll
   for (int pass = 0; pass < 3; ++pass) {
@@ -242,11 +241,18 @@ __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int 
     mask |= (uint32_t)(nb - 1) << shift;
     __syncthreads();
   }
-  // prefix is now the key of the count-th largest value; `remaining` of the entries equal
-  // to it are taken, from the low-index end.
-  // (compared as floats: the same order as the keys, with -0 equal to +0)
-  const float thr = __uint_as_float(raw_prefix_of(prefix, 0xffffffffu));
-  const uint32_t need_eq = remaining;
+  *thr_key = prefix;
+  *need_eq_out = remaining;
+}
+
+// Writes, ascending, the indices of the entries of x[0..m) above the threshold key and of the
+// first need_eq entries equal to it (compared as floats: the same order as the keys, with -0
+// equal to +0).
+__device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m, RowSplit rs,
+                                              uint32_t thr_key, uint32_t need_eq,
+                                              int32_t *__restrict__ out, SelShared &sh) {
+  const int tid = threadIdx.x;
+  const float thr = __uint_as_float(raw_prefix_of(thr_key, 0xffffffffu));
   uint32_t run_gt = 0, run_eq = 0;
   // the scalars before the first vector: every thread tracks the counts, thread 0 writes
   for (int j = 0; j < rs.lead; ++j) {
@@ -312,6 +318,16 @@ __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int 
   }
 }
 
+// Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
+// equal values taken from the low-index end.
+__device__ __forceinline__ void select_top_row(const float *__restrict__ x, int m, int count,
+                                               int32_t *__restrict__ out, SelShared &sh) {
+  const RowSplit rs = split_row(x, m);
+  uint32_t thr_key, need_eq;
+  radix_threshold(x, m, rs, count, sh, &thr_key, &need_eq);
+  emit_selected(x, m, rs, thr_key, need_eq, out, sh);
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims d, SeqTab t,
                                                              const float *__restrict__ pooled,
                                                              int32_t *__restrict__ idx) {
@@ -345,7 +361,10 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__
 // still reaches the number of slots left after the floors.  t is found digit by digit like
 // the per-row radix select, with one histogram per head (kept in the workspace) and a small
 // decision kernel per digit.  Search state per (layer, sequence): [0] prefix of t,
-// [2 .. 2+Hkv) keys above the prefix per head, [2+Hkv .. 2+2Hkv) keys equal to t per head.
+// [2 .. 2+Hkv) keys above the prefix per head, [2+Hkv .. 2+2Hkv) keys equal to t per head,
+// [2+2Hkv .. 2+3Hkv) how many of a head's keys equal to t it keeps, with bit 31 set when t is also the
+// head's own threshold (otherwise its floor reaches below t and the head runs its own radix search).
+__host__ __device__ constexpr int kAdaStateWords(int hkv) { return 2 + 3 * hkv; }
 __device__ __forceinline__ int ada_shift(int level) { return level == 0 ? 21 : level == 1 ? 10 : 0; }
 __device__ __forceinline__ int ada_bins(int level) { return level == 2 ? 1024 : 2048; }
 
@@ -365,7 +384,7 @@ __global__ __launch_bounds__(kSelThreads) void ada_hist_kernel(Dims d, SeqTab t,
   const float *x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
   const int shift = ada_shift(level), nb = ada_bins(level);
   const uint32_t mask = level == 0 ? 0u : level == 1 ? 0xffe00000u : 0xfffffc00u;
-  const uint32_t prefix = level == 0 ? 0u : state[(int64_t)ls * (2 + 2 * d.Hkv)];
+  const uint32_t prefix = level == 0 ? 0u : state[(int64_t)ls * kAdaStateWords(d.Hkv)];
   histogram_pass(x, max(m, 0), split_row(x, max(m, 0)), prefix, mask, shift, nb, sh);
   uint32_t *out = hist + (int64_t)unit * 2048;
   const bool neg = (prefix & 0x80000000u) == 0;
@@ -394,7 +413,7 @@ __global__ __launch_bounds__(kSelThreads) void ada_decide_kernel(Dims d, SeqTab 
   const int f = min(c_floor, C);
   const unsigned long long need = (unsigned long long)H * (unsigned)(C - f);
   uint32_t *hs = hist + (int64_t)ls * H * 2048;
-  uint32_t *st = state + (int64_t)ls * (2 + 2 * H);
+  uint32_t *st = state + (int64_t)ls * kAdaStateWords(H);
   const int shift = ada_shift(level), nb = ada_bins(level);
 
   // (i) each head's histogram becomes inclusive suffix sums (keys with this digit or a larger one)
@@ -466,6 +485,10 @@ __global__ __launch_bounds__(kSelThreads) void ada_decide_kernel(Dims d, SeqTab 
       open -= take;
       ho[h] = off;
       off += (int)((gt > f ? gt : f) + take) + d.w;
+      // the head keeps its keys above t and (floor part + take) of those equal to t, if its
+      // floor does not reach below t
+      const long long ties = (gt < f ? f - gt : 0) + take;
+      st[2 + 2 * H + h] = gt + eq >= f ? (0x80000000u | (uint32_t)ties) : 0u;
     }
     ho[H] = off;
   }
@@ -474,6 +497,7 @@ __global__ __launch_bounds__(kSelThreads) void ada_decide_kernel(Dims d, SeqTab 
 __global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab t,
                                                                  const float *__restrict__ pooled,
                                                                  const int32_t *__restrict__ head_off,
+                                                                 const uint32_t *__restrict__ state,
                                                                  int32_t *__restrict__ idx) {
   __shared__ SelShared sh;
   const int unit = blockIdx.x;
@@ -489,7 +513,11 @@ __global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab 
   const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
   int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + start;
   for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;
-  if (count > 0) select_top_row(row, m, count, out, sh);
+  if (count <= 0) return;
+  const uint32_t *st = state + (int64_t)ls * kAdaStateWords(d.Hkv);
+  const uint32_t known = st[2 + 2 * d.Hkv + g];
+  if (known & 0x80000000u) emit_selected(row, m, split_row(row, m), st[0], known & 0x7fffffffu, out, sh);
+  else select_top_row(row, m, count, out, sh);
 }
 
 // ----------------------------------------------------------------------------------
@@ -599,7 +627,7 @@ hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *poole
                        state, hist, head_off);
   }
   hipLaunchKernelGGL(select_ada_kernel, dim3(pairs * d.Hkv), dim3(kSelThreads), 0, st, d, pl.t, pooled,
-                     head_off, idx);
+                     head_off, state, idx);
   return hipGetLastError();
 }
 

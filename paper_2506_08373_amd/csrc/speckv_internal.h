@@ -94,7 +94,7 @@ hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_
                            hipStream_t st);
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st);
 // Shared layer budget: head offsets from a layer-wide threshold, then per-head selection.
-// hist: L*S*Hkv*2048 uint32, state: L*S*(2 + 2*Hkv) uint32 of scratch.
+// hist: L*S*Hkv*2048 uint32, state: L*S*(2 + 3*Hkv) uint32 of scratch.
 hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *pooled, int32_t *idx,
                              int32_t *head_off, uint32_t *hist, uint32_t *state, hipStream_t st);
 hipError_t launch_compact_ada(const Plan &pl, const void *k, const void *v, const int32_t *idx,
