@@ -826,3 +826,33 @@ def test_select_on_a_three_million_key_row(S):
     for g in range(2):
         want = orc.keep_indices(rows[g, :n - n_window].astype(np.float64), n, n_window, c_max)
         assert np.array_equal(got[g], want), g
+
+
+def test_two_streams_with_their_own_workspaces(S):
+    """The library keeps no state: calls enqueued on two streams at once, each with its own
+    workspace and outputs, give the results of the same calls made one after the other."""
+    wa = workloads.llama8b_layer(n_in=9000, c_max=300, n_layers=2, seed=41, name="stream_a")
+    wb = workloads.ragged_batch(n_layers=2, lo=500, hi=4000, n_seqs=3, seed=42, name="stream_b")
+    jobs = []
+    for w in (wa, wb):
+        t = workloads.generate(w)
+        tg = {x: t[x].cuda() for x in ("q", "k", "v")}
+        p = make_params(S, w)
+        KT, L, H, d = S.total_keep(p), w.n_layers, w.n_kv_heads, w.head_dim
+        outs = [(torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda"),
+                 torch.zeros((L, H * KT, d), dtype=w.torch_dtype, device="cuda"),
+                 torch.zeros((L, H * KT, d), dtype=w.torch_dtype, device="cuda")) for _ in range(2)]
+        jobs.append((p, tg, outs, alloc_ws(S, p)))
+    torch.cuda.synchronize()
+    for p, tg, outs, ws in jobs:                                   # reference: one after the other
+        S.speckv_compress(p, tg["q"], tg["k"], tg["v"], *outs[0], ws)
+        torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for _ in range(3):                                             # interleaved on two streams
+        for (p, tg, outs, ws), st in zip(jobs, streams):
+            with torch.cuda.stream(st):
+                S.speckv_compress(p, tg["q"], tg["k"], tg["v"], *outs[1], ws)
+    torch.cuda.synchronize()
+    for p, tg, outs, ws in jobs:
+        for a, b in zip(outs[0], outs[1]):
+            assert torch.equal(a, b)
