@@ -14,7 +14,9 @@ constexpr int kTargetWorkgroups = 1024;             // scoring grid: at least ab
 constexpr int kChunkFloor = 8192;                   // chunks are not shortened below this to balance the grid
 constexpr int kWorkgroupCost = 190;                 // fixed cost of a scoring workgroup, in keys (measured)
 constexpr int kCUs = 256;                           // compute units of an MI355X
-constexpr int kChunkAlign = 128;                    // chunk = whole LDS key tiles
+constexpr int kChunkAlign = 256;                    // chunk = whole LDS key tiles (the largest tile)
+constexpr int kChunkMin = 512;                      // shortest chunk
+constexpr int kChunkSmallCap = 4096;                // longest chunk that small problems are given
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -96,7 +98,8 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (units > 65535) return SPECKV_ERR_UNSUPPORTED;
   // Keys [0, tail0) of a sequence are complete LDS tiles visible to every observation row
   // (key <= m); they are cut into chunks of KC keys.  The rest is one masked tail chunk.
-  const int kt = d.D * d.elt <= 256 ? 128 : 64;
+  const int rowb = d.D * d.elt;
+  const int kt = rowb <= 128 ? 256 : rowb <= 256 ? 128 : 64;          // keys per LDS tile of the scoring kernels
   int64_t fast_keys = 0;
   for (int s = 0; s < d.S; ++s) {
     const int n_s = t.cu[s + 1] - t.cu[s];
@@ -135,9 +138,9 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
     }
   }
   int64_t kc_few = align_up((fast_keys + few - 1) / few, kChunkAlign);
-  if (kc_few > 32 * kChunkAlign) kc_few = 32 * kChunkAlign;
+  if (kc_few > kChunkSmallCap) kc_few = kChunkSmallCap;
   if (kc < kc_few) kc = kc_few;
-  if (kc < 4 * kChunkAlign) kc = 4 * kChunkAlign;
+  if (kc < kChunkMin) kc = kChunkMin;
   g.KC = (int32_t)kc;
   t.cc[0] = 0;
   for (int s = 0; s < d.S; ++s) t.cc[s + 1] = t.cc[s] + (t.tail0[s] + g.KC - 1) / g.KC;

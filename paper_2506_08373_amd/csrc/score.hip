@@ -90,7 +90,7 @@ struct Tile {
   static constexpr int ROWB = D * ELT;          // bytes per key / query row
   static constexpr int C16 = ROWB / 16;         // 16-byte chunks per row
   static constexpr int NCS = C16 / 2;           // chunk steps (each lane half owns NCS chunks)
-  static constexpr int KT = ROWB <= 256 ? 128 : 64;   // keys per LDS tile
+  static constexpr int KT = ROWB <= 128 ? 256 : ROWB <= 256 ? 128 : 64;   // keys per LDS tile (32 KiB)
   static constexpr int TILE_BYTES = KT * ROWB;
   static constexpr int RPB = ROWB >= 256 ? 1 : 256 / ROWB;   // rows per 256-byte bank sweep
   static constexpr int SWZ = (C16 < 16 ? C16 : 16) - 1;      // xor mask applied to the chunk index

@@ -93,14 +93,62 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
 }
 
 // One output row that merges every plane (all layers, heads, row super-blocks) of a
-// single-sequence call: planes are consecutive rows of n_in floats.
-__global__ __launch_bounds__(kPoolThreads) void reduce_pool_all_kernel(
+// single-sequence call: planes are consecutive rows of n_in floats, all merged by one op (sum or
+// max).  There can be hundreds of planes, so a workgroup takes a short tile of keys and its four
+// wavefronts each merge a quarter of the planes; the quarters are combined in a fixed order.
+constexpr int kAllTile = 64, kAllSlices = 4;
+
+__global__ __launch_bounds__(kAllTile * kAllSlices) void reduce_pool_all_kernel(
     int n_in, int n_window, int pool_k, int pool_avg, PlaneMerge pm, const float *__restrict__ planes,
     float *__restrict__ raw, float *__restrict__ pooled) {
-  __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
-  const int j0 = blockIdx.x * kPoolTile;
+  __shared__ float part[kAllSlices][kAllTile + SPECKV_MAX_POOL_K + 1];
+  const int j0 = blockIdx.x * kAllTile;
   if (j0 >= n_in) return;
-  reduce_pool_tile(planes, pm, raw, pooled, n_in, n_in - n_window, pool_k, pool_avg, j0, tile);
+  const int half = pool_k / 2, span = kAllTile + 2 * half;
+  const int slice = threadIdx.x / kAllTile, lane = threadIdx.x % kAllTile;
+  const int n_planes = pm.n_outer * pm.n_inner;
+  const int per_slice = (n_planes + kAllSlices - 1) / kAllSlices;
+  const int o0 = slice * per_slice, o1 = min(n_planes, o0 + per_slice);
+  for (int x = lane; x < span; x += kAllTile) {
+    const int jj = j0 - half + x;
+    float acc = 0.f;                                       // scores are non-negative: 0 is neutral for max
+    if (jj >= 0 && jj < n_in) {
+      const float *p = planes + jj;
+#pragma unroll 8
+      for (int o = o0; o < o1; ++o) {
+        const float y = p[(int64_t)o * pm.plane_stride];
+        acc = pm.outer_max ? fmaxf(acc, y) : acc + y;
+      }
+    }
+    part[slice][x] = acc;
+  }
+  __syncthreads();
+  float *tile = part[0];
+  for (int x = threadIdx.x; x < span; x += kAllTile * kAllSlices) {
+    float v = part[0][x];
+#pragma unroll
+    for (int s2 = 1; s2 < kAllSlices; ++s2) v = pm.outer_max ? fmaxf(v, part[s2][x]) : v + part[s2][x];
+    tile[x] = v;
+  }
+  __syncthreads();
+  const int m = n_in - n_window;
+  for (int x = threadIdx.x; x < kAllTile; x += kAllTile * kAllSlices) {
+    const int j = j0 + x;
+    if (j >= n_in) break;
+    if (raw != nullptr) raw[j] = tile[x + half];
+    float best = 0.f;
+    if (j < m) {
+      const int lo = max(0, j - half), hi = min(m - 1, j + half);
+      best = tile[lo - j0 + half];
+      if (pool_avg) {
+        for (int jj = lo + 1; jj <= hi; ++jj) best += tile[jj - j0 + half];
+        best /= (float)pool_k;                            // zeros outside [0, m) count in the divisor
+      } else {
+        for (int jj = lo + 1; jj <= hi; ++jj) best = fmaxf(best, tile[jj - j0 + half]);
+      }
+    }
+    pooled[j] = best;
+  }
 }
 
 // ----------------------------------------------------------------------------------
@@ -586,7 +634,7 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
                                   hipStream_t st) {
   const Dims &d = pl.d;
   const int n_in = (int)d.T;
-  const int tiles = (n_in + kPoolTile - 1) / kPoolTile;
+  const int tiles = (n_in + kAllTile - 1) / kAllTile;
   // every plane (row super-block, layer, head) merges with one op: all sums, or all maxima
   PlaneMerge pm;
   pm.n_inner = 1;
@@ -594,17 +642,17 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
   pm.inner_max = 0;
   pm.outer_max = d.reduce_max && d.head_max;
   pm.plane_stride = n_in;
-  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kPoolThreads), 0, st, n_in, d.w,
+  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kAllTile * kAllSlices), 0, st, n_in, d.w,
                      d.pool_k, d.pool_avg, pm, planes, raw, pooled);
   return hipGetLastError();
 }
 
 hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_window, int32_t pool_k,
                            hipStream_t st) {
-  const int tiles = (n_in + kPoolTile - 1) / kPoolTile;
+  const int tiles = (n_in + kAllTile - 1) / kAllTile;
   PlaneMerge pm;
   pm.n_inner = 1; pm.n_outer = 1; pm.inner_max = 0; pm.outer_max = 0; pm.plane_stride = n_in;
-  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kPoolThreads), 0, st, n_in, n_window,
+  hipLaunchKernelGGL(reduce_pool_all_kernel, dim3(tiles), dim3(kAllTile * kAllSlices), 0, st, n_in, n_window,
                      pool_k, 0, pm, in, (float *)nullptr, out);
   return hipGetLastError();
 }
