@@ -62,7 +62,9 @@ typedef enum {
   SPECKV_ERR_RUNTIME = -4      /* the HIP runtime refused a launch                          */
 } speckv_status;
 
-typedef enum { SPECKV_BF16 = 0, SPECKV_F32 = 1 } speckv_dtype;
+/* Number type of q, k and v.  Products are exact in fp32 for all three; accumulation, softmax and
+ * scores are fp32 (the paper does not fix a precision). */
+typedef enum { SPECKV_BF16 = 0, SPECKV_F32 = 1, SPECKV_F16 = 2 } speckv_dtype;
 
 /* Reduction over the observation rows of one query head (Alg. 1 reduce step).  SUM is Eq. 1's
  * mean times a constant; MAX is the listing's MaxReduce (hyper-parameter table "Reduction =

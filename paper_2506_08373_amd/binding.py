@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libspeckv.so")
 _lib = None
 
-SPECKV_BF16, SPECKV_F32 = 0, 1
+SPECKV_BF16, SPECKV_F32, SPECKV_F16 = 0, 1, 2
 _STATUS = {0: "ok", -1: "invalid argument", -2: "unsupported configuration",
            -3: "workspace missing, misaligned or too small", -4: "HIP runtime error"}
 
@@ -133,7 +133,7 @@ class SpecKVParams:
         self.c = _CParams(
             n_seqs=S, n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
             n_window=n_window, n_lookahead=n_lookahead, pool_k=pool_k, c_max=c_max, sm_scale=sm_scale,
-            dtype={torch.bfloat16: SPECKV_BF16, torch.float32: SPECKV_F32}[dtype],
+            dtype={torch.bfloat16: SPECKV_BF16, torch.float32: SPECKV_F32, torch.float16: SPECKV_F16}[dtype],
             cu_seqlens=ctypes.cast(self._cu, ctypes.POINTER(ctypes.c_int32)), n_in=0,
             q_stride_layer=q_strides[0], q_stride_seq=q_strides[1], q_stride_row=q_strides[2],
             q_stride_head=q_strides[3], kv_stride_layer=kv_strides[0], kv_stride_token=kv_strides[1],

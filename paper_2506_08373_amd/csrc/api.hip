@@ -30,7 +30,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (p->n_window < 0 || p->n_lookahead < 0 || p->n_window + (int64_t)p->n_lookahead < 1) return SPECKV_ERR_INVALID_ARG;
   if (p->pool_k < 1 || p->pool_k % 2 == 0 || p->c_max < 0) return SPECKV_ERR_INVALID_ARG;
   if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return SPECKV_ERR_INVALID_ARG;
-  if (p->dtype != SPECKV_BF16 && p->dtype != SPECKV_F32) return SPECKV_ERR_INVALID_ARG;
+  if (p->dtype != SPECKV_BF16 && p->dtype != SPECKV_F32 && p->dtype != SPECKV_F16) return SPECKV_ERR_INVALID_ARG;
   if (p->reduce_op != SPECKV_REDUCE_SUM && p->reduce_op != SPECKV_REDUCE_MAX) return SPECKV_ERR_INVALID_ARG;
   if (p->pool_op != SPECKV_POOL_MAX && p->pool_op != SPECKV_POOL_AVG) return SPECKV_ERR_INVALID_ARG;
   if (p->n_seqs > SPECKV_MAX_SEQS) return SPECKV_ERR_UNSUPPORTED;
@@ -39,7 +39,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (one_row_per_call && p->n_seqs != 1) return SPECKV_ERR_UNSUPPORTED;
 
   d.L = p->n_layers; d.S = p->n_seqs; d.Hq = p->n_q_heads; d.Hkv = p->n_kv_heads;
-  d.G = d.Hq / d.Hkv; d.D = p->head_dim; d.elt = p->dtype == SPECKV_BF16 ? 2 : 4;
+  d.G = d.Hq / d.Hkv; d.D = p->head_dim; d.elt = p->dtype == SPECKV_F32 ? 4 : 2; d.dt = p->dtype;
   d.w = p->n_window; d.a = p->n_lookahead; d.R = d.w + d.a;
   d.pool_k = p->pool_k; d.c_max = p->c_max; d.sm_scale = p->sm_scale;
   d.reduce_max = p->reduce_op == SPECKV_REDUCE_MAX; d.pool_avg = p->pool_op == SPECKV_POOL_AVG;

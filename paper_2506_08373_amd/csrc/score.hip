@@ -23,7 +23,7 @@
 // so a lane holds 16 rows of ONE key and the column sum is an in-lane add, one cross-half add and
 // a cross-wave add through LDS.  No atomics anywhere: results are bit-reproducible.
 //
-// MFMA operand layout used (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_32x32x2_f32): lane l holds
+// MFMA operand layout used (v_mfma_f32_32x32x16_bf16, v_mfma_f32_32x32x16_f16, v_mfma_f32_32x32x2_f32): lane l holds
 // row (A) or column (B) l%32 and the k-slice selected by l/32; the result register i of lane l
 // is element (8*(i/4) + 4*(l/32) + i%4, l%32).  Both operands take their k-slices from the same
 // 16-byte chunks of the head dimension (half l/32 reads chunks [half*NCS, half*NCS+NCS)), so the
@@ -36,6 +36,7 @@ namespace speckv {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
 
@@ -67,17 +68,28 @@ __device__ inline float max_other_half(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int ELT>
+// Number types (values of speckv_dtype) and their element size.
+constexpr int kBf16 = SPECKV_BF16, kF32 = SPECKV_F32, kF16 = SPECKV_F16;
+constexpr int elt_bytes(int dt) { return dt == kF32 ? 4 : 2; }
+
+// One 16-byte chunk of the head dimension per lane half: 8 bf16/f16 or 4 f32 products per row pair.
+template <int DT>
 __device__ inline f32x16 mma_chunk(u32x4 a, u32x4 b, f32x16 acc);
 
 template <>
-__device__ inline f32x16 mma_chunk<2>(u32x4 a, u32x4 b, f32x16 acc) {
+__device__ inline f32x16 mma_chunk<kBf16>(u32x4 a, u32x4 b, f32x16 acc) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
 
 template <>
-__device__ inline f32x16 mma_chunk<4>(u32x4 a, u32x4 b, f32x16 acc) {
+__device__ inline f32x16 mma_chunk<kF16>(u32x4 a, u32x4 b, f32x16 acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+}
+
+template <>
+__device__ inline f32x16 mma_chunk<kF32>(u32x4 a, u32x4 b, f32x16 acc) {
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
@@ -109,8 +121,9 @@ constexpr size_t score_lds_bytes() {
 //   MASKED  false: every tile of the chunk is complete and visible to every row (key <= m), the
 //           loop body is straight-line code without any bounds or mask logic;
 //           true: the tail of a sequence (keys that window rows may not see, end of sequence)
-template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
 __device__ __forceinline__ void score_body(const ScoreArgs &A) {
+  constexpr int ELT = elt_bytes(DT);
   using TL = Tile<ELT, D>;
   constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
   constexpr int RSB = NW * MB * 32;
@@ -334,7 +347,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
           for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
             for (int rb = 0; rb < NACT; ++rb)
-              acc[rb] = PASS == 1 ? mma_chunk<ELT>(bf[cs], qf[rb][cs], acc[rb]) : mma_chunk<ELT>(qf[rb][cs], bf[cs], acc[rb]);
+              acc[rb] = PASS == 1 ? mma_chunk<DT>(bf[cs], qf[rb][cs], acc[rb]) : mma_chunk<DT>(qf[rb][cs], bf[cs], acc[rb]);
           if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
           if (PASS == 1) {
 #pragma unroll
@@ -404,7 +417,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
             if (rb >= nact) continue;
             f32x16 acc = {0};
 #pragma unroll
-            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(bf[cs], qf[rb][cs], acc);
+            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<DT>(bf[cs], qf[rb][cs], acc);
             // lane: query row (wv*MB+rb)*32 + l32; keys tk0 + kb*32 + 8*(i/4) + 4*half + i%4
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -431,7 +444,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
             if (rb >= nact) continue;
             f32x16 acc = {0};
 #pragma unroll
-            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<ELT>(qf[rb][cs], bf[cs], acc);
+            for (int cs = 0; cs < NCS; ++cs) acc = mma_chunk<DT>(qf[rb][cs], bf[cs], acc);
             // lane: key tk0 + kb*32 + l32; rows (wv*MB+rb)*32 + 8*(i/4) + 4*half + i%4
             float p[16];
 #pragma unroll
@@ -488,14 +501,14 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
 
 // The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
 // then schedules its online-softmax step more freely); the column sweep does better without.
-template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_kernel_rows(ScoreArgs A) {
-  score_body<ELT, D, MB, NW, PASS, RED, MASKED>(A);
+  score_body<DT, D, MB, NW, PASS, RED, MASKED>(A);
 }
 
-template <int ELT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
 __global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
-  score_body<ELT, D, MB, NW, PASS, RED, MASKED>(A);
+  score_body<DT, D, MB, NW, PASS, RED, MASKED>(A);
 }
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
@@ -571,7 +584,7 @@ hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_
   return hipGetLastError();
 }
 
-template <int ELT, int D, int MB, int NW, int PASS, int RED>
+template <int DT, int D, int MB, int NW, int PASS, int RED>
 hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
   const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
   hipError_t e;
@@ -580,19 +593,19 @@ hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
     const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS;
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs), block(NW * 64);
-    if (PASS == 1 && NW == 8) e = launch_one(score_kernel_rows<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
-    else e = launch_one(score_kernel_cols<ELT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    if (PASS == 1 && NW == 8) e = launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    else e = launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     if (e != hipSuccess) return e;
   }
-  return launch_one(score_kernel_cols<ELT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
+  return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
 }
 
-template <int ELT, int D, int MB, int NW>
+template <int DT, int D, int MB, int NW>
 hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
-  const size_t lds = score_lds_bytes<ELT, D, MB, NW>();
+  const size_t lds = score_lds_bytes<elt_bytes(DT), D, MB, NW>();
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;
-  if (A.lse_in == nullptr && (e = launch_sweep<ELT, D, MB, NW, 1, 0>(A, lds, st)) != hipSuccess) return e;
+  if (A.lse_in == nullptr && (e = launch_sweep<DT, D, MB, NW, 1, 0>(A, lds, st)) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return e;
   if (A.lse_in == nullptr) {
     hipLaunchKernelGGL(lse_combine_kernel, dim3(A.d.L * A.d.Hkv * A.g.RS * (A.g.RSB / kMergeRows), A.d.S),
@@ -602,20 +615,20 @@ hipError_t launch_passes(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], st)) != hipSuccess) return e;
-  e = A.d.reduce_max ? launch_sweep<ELT, D, MB, NW, 2, 1>(A, lds, st) : launch_sweep<ELT, D, MB, NW, 2, 0>(A, lds, st);
+  e = A.d.reduce_max ? launch_sweep<DT, D, MB, NW, 2, 1>(A, lds, st) : launch_sweep<DT, D, MB, NW, 2, 0>(A, lds, st);
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[3], st)) != hipSuccess) return e;
   return hipSuccess;
 }
 
-template <int ELT, int D>
+template <int DT, int D>
 hipError_t dispatch_geom(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
   const int code = A.g.NW * 10 + A.g.MB;
   switch (code) {
-    case 41: return launch_passes<ELT, D, 1, 4>(A, st, ev);
-    case 81: return launch_passes<ELT, D, 1, 8>(A, st, ev);
+    case 41: return launch_passes<DT, D, 1, 4>(A, st, ev);
+    case 81: return launch_passes<DT, D, 1, 8>(A, st, ev);
     case 82:
-      if constexpr (D * ELT <= 256) return launch_passes<ELT, D, 2, 8>(A, st, ev);
+      if constexpr (D * elt_bytes(DT) <= 256) return launch_passes<DT, D, 2, 8>(A, st, ev);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
@@ -629,10 +642,11 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
   A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in;
-  if (pl.d.elt == 2) {
-    return pl.d.D == 128 ? dispatch_geom<2, 128>(A, st, events) : dispatch_geom<2, 64>(A, st, events);
+  switch (pl.d.dt) {
+    case SPECKV_BF16: return pl.d.D == 128 ? dispatch_geom<kBf16, 128>(A, st, events) : dispatch_geom<kBf16, 64>(A, st, events);
+    case SPECKV_F16: return pl.d.D == 128 ? dispatch_geom<kF16, 128>(A, st, events) : dispatch_geom<kF16, 64>(A, st, events);
+    default: return pl.d.D == 128 ? dispatch_geom<kF32, 128>(A, st, events) : dispatch_geom<kF32, 64>(A, st, events);
   }
-  return pl.d.D == 128 ? dispatch_geom<4, 128>(A, st, events) : dispatch_geom<4, 64>(A, st, events);
 }
 
 }  // namespace speckv

@@ -21,7 +21,8 @@ struct SeqTab {
 };
 
 struct Dims {
-  int32_t L, S, Hq, Hkv, G, D, elt;       // elt = bytes per element (2 bf16, 4 f32)
+  int32_t L, S, Hq, Hkv, G, D, elt;       // elt = bytes per element (2 bf16 / f16, 4 f32)
+  int32_t dt;                              // speckv_dtype of q, k, v
   int32_t w, a, R, M;                      // M = G * R rows per KV group
   int32_t pool_k, c_max;
   int32_t reduce_max;                      // 1: max over the rows of a head instead of the sum

@@ -100,6 +100,14 @@ def test_null_misaligned_and_workspace_errors(lib):
     assert lib.speckv_compress_events(p.ref(), ok, ok, ok, ok, ok, ok, ok, need, None, None, 7) == -1
 
 
+def test_number_types(lib):
+    for dt in (torch.bfloat16, torch.float16, torch.float32):
+        assert S.workspace_bytes(base_params(dtype=dt)) > 0
+    p = base_params()
+    p.c.dtype = 3                                            # not a speckv_dtype
+    assert S.workspace_bytes(p) == 0
+
+
 def test_shared_budget_entry_points_validate(lib):
     p = base_params()
     ok = 256

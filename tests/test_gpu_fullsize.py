@@ -70,7 +70,7 @@ def check_structure_everywhere(w, data, idx, k_out, v_out):
         hit = (rows[..., None, :C] == planted[..., :, None]).any(-1)       # [L, H, P]
         assert bool(hit.all()), "a planted heavy hitter was dropped"
         # compaction is a bit copy of the selected rows
-        view = torch.int16 if w.dtype == "bf16" else torch.int32
+        view = torch.int16 if w.dtype != "f32" else torch.int32
         ksrc = data["k"][:, cu[s]:cu[s + 1]].view(view)                    # [L, n, H, d]
         vsrc = data["v"][:, cu[s]:cu[s + 1]].view(view)
         ko = k_out[:, H * ck[s]: H * ck[s + 1]].view(view).reshape(w.n_layers, H, nk, w.head_dim)

@@ -152,12 +152,12 @@ def check_full_path(S, w, c_max=None, pool_k=None, expect_exact=None, reduce="su
             n = w.seq_lens[s]
             r = ref[layer][s]
             idx_ls = split_keep(w, idx_h, layer, s, c_eff)
-            ko = split_keep(w, k_out.view(torch.int16 if w.dtype == "bf16" else torch.int32).numpy(),
+            ko = split_keep(w, k_out.view(torch.int16 if w.dtype != "f32" else torch.int32).numpy(),
                             layer, s, c_eff, trailing=(w.head_dim,))
-            vo = split_keep(w, v_out.view(torch.int16 if w.dtype == "bf16" else torch.int32).numpy(),
+            vo = split_keep(w, v_out.view(torch.int16 if w.dtype != "f32" else torch.int32).numpy(),
                             layer, s, c_eff, trailing=(w.head_dim,))
-            kin = t["k"][layer, cu[s]:cu[s + 1]].view(torch.int16 if w.dtype == "bf16" else torch.int32).numpy()
-            vin = t["v"][layer, cu[s]:cu[s + 1]].view(torch.int16 if w.dtype == "bf16" else torch.int32).numpy()
+            kin = t["k"][layer, cu[s]:cu[s + 1]].view(torch.int16 if w.dtype != "f32" else torch.int32).numpy()
+            vin = t["v"][layer, cu[s]:cu[s + 1]].view(torch.int16 if w.dtype != "f32" else torch.int32).numpy()
             for g in range(H):
                 total += 1
                 exact += assert_indices_valid(idx_ls[g], r["pooled"][g], n, w.n_window, c_eff,
@@ -856,3 +856,13 @@ def test_two_streams_with_their_own_workspaces(S):
     for p, tg, outs, ws in jobs:
         for a, b in zip(outs[0], outs[1]):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("head_dim,group", [(128, 4), (64, 3)])
+def test_half_precision_inputs(S, head_dim, group):
+    """fp16 Q/K/V (the number type of the GPTQ/AWQ-quantised targets): same path, f16 MFMA."""
+    w = workloads.SpecKVWorkload(
+        name="f16", n_layers=2, n_q_heads=2 * group, n_kv_heads=2, head_dim=head_dim, seq_lens=(2500, 700),
+        n_window=16, n_lookahead=24, pool_k=7, c_max=200, dtype="f16", sm_scale=1.0 / math.sqrt(head_dim),
+        n_planted=4, channel_scale=(0.5, 4.0), seed=51)
+    check_full_path(S, w)

@@ -56,7 +56,7 @@ class SpecKVWorkload:
     n_lookahead: int
     pool_k: int
     c_max: int
-    dtype: str  # "bf16" or "f32"
+    dtype: str  # "bf16", "f16" or "f32"
     sm_scale: float
     q_gain: float = 1.0
     n_planted: int = 0
@@ -93,7 +93,7 @@ class SpecKVWorkload:
 
     @property
     def torch_dtype(self) -> torch.dtype:
-        return {"bf16": torch.bfloat16, "f32": torch.float32}[self.dtype]
+        return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[self.dtype]
 
     @property
     def key_units(self) -> int:
