@@ -142,7 +142,9 @@ speckv_status speckv_score_lse(const speckv_params *p, const void *q, const void
 /* Selection (Alg. 1 "Select KVs"; Fig. 2: window always retained).  For every (layer,
  * sequence, KV head) writes the min(c_max, m) candidates with the largest pooled score
  * (equal scores: smaller index first), in ascending order, followed by m..n_in-1.
- * `pooled` must not contain NaN.  Layout: "idx" above. */
+ * `pooled` must not contain NaN.  Layout: "idx" above.  The workspace is optional: with NULL every
+ * row is ranked by one workgroup; with a workspace of speckv_workspace_bytes, calls with few rows
+ * of 2^18 keys or more spread each row over several workgroups (same result). */
 speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
                             void *workspace, size_t workspace_bytes, void *stream);
 

@@ -1,6 +1,7 @@
 // Host side of libspeckv: argument validation, launch planning, workspace carve-up and the
 // extern "C" entry points declared in speckv.h.  Nothing here touches the device except
 // kernel launches on the caller's stream.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 
@@ -15,6 +16,9 @@ constexpr int kChunkFloor = 8192;                   // chunks are not shortened 
 constexpr int kWorkgroupCost = 190;                 // fixed cost of a scoring workgroup, in keys (measured)
 constexpr int kCUs = 256;                           // compute units of an MI355X
 constexpr int kChunkAlign = 256;                    // chunk = whole LDS key tiles (the largest tile)
+constexpr int kSelSplitMinKeys = 1 << 18;            // rows at least this long may be ranked by several workgroups
+constexpr int kSelSplitWorkgroups = 512;            // ... when the call has fewer than half this many rows
+constexpr int kSelSplitMaxParts = 64;
 constexpr int kChunkMin = 512;                      // shortest chunk
 constexpr int kChunkSmallCap = 4096;                // longest chunk that small problems are given
 
@@ -156,6 +160,22 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   pl->off_pooled = take(one_row_per_call ? (size_t)d.T * sizeof(float) : (size_t)d.L * d.Hkv * d.T * sizeof(float));
   pl->off_pooled2 = take(one_row_per_call ? (size_t)d.T * sizeof(float) : 0);
   pl->off_sel = take(one_row_per_call ? (size_t)(top_k > 0 ? top_k : 0) * sizeof(int32_t) : 0);
+  // Selection: one workgroup per row unless the call has few, long rows; then each row is cut into
+  // parts so that about kSelSplitWorkgroups workgroups share the ranking.
+  pl->sel_parts = 1; pl->sel_part_len = 0; pl->off_sel_hist = 0; pl->off_sel_state = 0;
+  if (!one_row_per_call) {
+    const int64_t rows = (int64_t)d.L * d.S * d.Hkv;
+    int max_m = 0;
+    for (int s = 0; s < d.S; ++s) max_m = std::max(max_m, t.cu[s + 1] - t.cu[s] - d.w);
+    if (max_m >= kSelSplitMinKeys && rows * 2 <= kSelSplitWorkgroups) {
+      int parts = (int)(kSelSplitWorkgroups / rows);
+      if (parts > kSelSplitMaxParts) parts = kSelSplitMaxParts;
+      pl->sel_part_len = (int32_t)align_up((max_m + parts - 1) / parts, 1024);
+      pl->sel_parts = (max_m + pl->sel_part_len - 1) / pl->sel_part_len;
+      pl->off_sel_hist = take((size_t)rows * pl->sel_parts * 2048 * sizeof(uint32_t));
+      pl->off_sel_state = take((size_t)rows * (2 + 2 * (size_t)pl->sel_parts) * sizeof(uint32_t));
+    }
+  }
   pl->total = off;
   pl->off_ada_hist = take((size_t)d.L * d.S * d.Hkv * 2048 * sizeof(uint32_t));
   pl->off_ada_state = take((size_t)d.L * d.S * (2 + 3 * (size_t)d.Hkv) * sizeof(uint32_t));
@@ -244,13 +264,22 @@ speckv_status speckv_score_lse(const speckv_params *p, const void *q, const void
 
 speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
                             void *workspace, size_t workspace_bytes, void *stream) {
-  (void)workspace; (void)workspace_bytes;     // selection keeps its scratch in LDS
   Plan pl;
   speckv_status st = build_plan(p, &pl, false, 0);
   if (st != SPECKV_OK) return st;
   if (pooled == nullptr || idx == nullptr) return SPECKV_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(pooled) & 3u) || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SPECKV_ERR_INVALID_ARG;
-  return from_hip(launch_select(pl, pooled, idx, static_cast<hipStream_t>(stream)));
+  // The workspace is optional here: without it every row is ranked by one workgroup (scratch in
+  // LDS); with it, calls with few and very long rows spread each row over several workgroups.
+  uint32_t *hist = nullptr, *state = nullptr;
+  if (workspace != nullptr) {
+    if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
+    if (pl.sel_parts > 1) {
+      hist = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + pl.off_sel_hist);
+      state = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + pl.off_sel_state);
+    }
+  }
+  return from_hip(launch_select(pl, pooled, idx, hist, state, static_cast<hipStream_t>(stream)));
 }
 
 speckv_status speckv_compact(const speckv_params *p, const void *k, const void *v, const int32_t *idx,
@@ -286,7 +315,8 @@ static speckv_status compress_impl(const speckv_params *p, const void *q, const 
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
-  if ((e = launch_select(pl, pooled, idx, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_select(pl, pooled, idx, reinterpret_cast<uint32_t *>(ws + pl.off_sel_hist),
+                         reinterpret_cast<uint32_t *>(ws + pl.off_sel_state), hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[5], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_compact(pl, k, v, idx, k_out, v_out, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[6], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;

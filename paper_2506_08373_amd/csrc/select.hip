@@ -296,17 +296,19 @@ __device__ __forceinline__ void radix_threshold(const float *__restrict__ x, int
 // Writes, ascending, the indices of the entries of x[0..m) above the threshold key and of the
 // first need_eq entries equal to it (compared as floats: the same order as the keys, with -0
 // equal to +0).
+// x may be a slice of a longer row: index_base is the row index of x[0] and run_gt / run_eq
+// start at the numbers of entries above / equal to the threshold that precede the slice.
 __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m, RowSplit rs,
                                               uint32_t thr_key, uint32_t need_eq,
-                                              int32_t *__restrict__ out, SelShared &sh) {
+                                              int32_t *__restrict__ out, SelShared &sh,
+                                              uint32_t run_gt = 0, uint32_t run_eq = 0, int index_base = 0) {
   const int tid = threadIdx.x;
   const float thr = __uint_as_float(raw_prefix_of(thr_key, 0xffffffffu));
-  uint32_t run_gt = 0, run_eq = 0;
   // the scalars before the first vector: every thread tracks the counts, thread 0 writes
   for (int j = 0; j < rs.lead; ++j) {
     const float xj = x[j];
     const bool is_gt = xj > thr, is_eq = xj == thr;
-    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = j;
+    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = index_base + j;
     run_gt += is_gt;
     run_eq += is_eq;
   }
@@ -346,7 +348,7 @@ __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m
         for (int b = 0; b < 4 * kSelVec; ++b) {
           const bool is_gt = (gt_bits >> b) & 1u, is_eq = (eq_bits >> b) & 1u;
           if (is_gt || (is_eq && eq_before < need_eq))
-            out[gt_before + min(eq_before, need_eq)] = rs.lead + 4 * vb + b;
+            out[gt_before + min(eq_before, need_eq)] = index_base + rs.lead + 4 * vb + b;
           gt_before += is_gt;
           eq_before += is_eq;
         }
@@ -360,7 +362,7 @@ __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m
   for (int j = rs.tail0; j < m; ++j) {
     const float xj = x[j];
     const bool is_gt = xj > thr, is_eq = xj == thr;
-    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = j;
+    if (tid == 0 && (is_gt || (is_eq && run_eq < need_eq))) out[run_gt + min(run_eq, need_eq)] = index_base + j;
     run_gt += is_gt;
     run_eq += is_eq;
   }
@@ -399,6 +401,128 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__
                                                                  int32_t *__restrict__ sel) {
   __shared__ SelShared sh;
   if (count > 0) select_top_row(row, m, count, sel, sh);
+}
+
+// ----------------------------------------------------------------------------------
+// long rows, few rows: a row split over several workgroups
+// ----------------------------------------------------------------------------------
+// One workgroup ranks about 128K keys in 55 us; a call with a handful of rows of a million keys
+// would leave the other CUs idle for most of a millisecond.  Such rows are cut into P parts.
+// Per digit, msel_hist_kernel histograms every part and msel_decide_kernel (one workgroup per
+// row) adds the parts, extends the threshold prefix and keeps, per part, the number of keys above
+// it; after the last digit it also knows the keys equal to the threshold per part, so that
+// msel_emit_kernel can place every part's output without another counting pass.
+// State per row: [0] prefix, [1] remaining, [2 .. 2+P) keys above per part, [2+P .. 2+2P) equal.
+struct RowRef { const float *x; int32_t *out; int m, count; };
+__device__ __forceinline__ RowRef row_of(const Dims &d, const SeqTab &t, int row, const float *pooled,
+                                         int32_t *idx) {
+  const int g = row % d.Hkv;
+  const int s = (row / d.Hkv) % d.S;
+  const int layer = row / (d.Hkv * d.S);
+  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int n_keep = t.ck[s + 1] - t.ck[s];
+  RowRef r;
+  r.x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  r.out = idx ? idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + (int64_t)g * n_keep : nullptr;
+  r.m = n_s - d.w;
+  r.count = n_keep - d.w;
+  return r;
+}
+
+__global__ __launch_bounds__(kSelThreads) void msel_hist_kernel(Dims d, SeqTab t, const float *__restrict__ pooled,
+                                                                int level, int P, int part_len,
+                                                                const uint32_t *__restrict__ state,
+                                                                uint32_t *__restrict__ hist) {
+  __shared__ SelShared sh;
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x / P, part = blockIdx.x % P;
+  const RowRef r = row_of(d, t, row, pooled, nullptr);
+  const int start = part * part_len;
+  const int len = max(0, min(part_len, r.m - start));
+  const int shift = level == 0 ? 21 : level == 1 ? 10 : 0, nb = level == 2 ? 1024 : 2048;
+  const uint32_t mask = level == 0 ? 0u : level == 1 ? 0xffe00000u : 0xfffffc00u;
+  const uint32_t prefix = level == 0 ? 0u : state[(int64_t)row * (2 + 2 * P)];
+  const float *x = r.x + start;
+  histogram_pass(x, len, split_row(x, len), prefix, mask, shift, nb, sh);
+  uint32_t *out = hist + (int64_t)blockIdx.x * 2048;
+  const bool neg = (prefix & 0x80000000u) == 0;
+  for (int b = tid; b < 2048; b += kSelThreads) {       // b: ordered digit
+    uint32_t c = 0;
+    if (b < nb) {
+      const int rd = raw_digit(b, level, nb, neg);
+#pragma unroll
+      for (int cp = 0; cp < kHistCopies; ++cp) c += sh.hist[cp * 2048 + rd];
+    }
+    out[b] = c;
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void msel_decide_kernel(Dims d, SeqTab t, int level, int P,
+                                                                  uint32_t *__restrict__ state,
+                                                                  const uint32_t *__restrict__ hist) {
+  __shared__ uint32_t wave_tot[kSelWaves];
+  __shared__ uint32_t found[2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x;
+  const RowRef r = row_of(d, t, row, nullptr, nullptr);
+  if (r.count <= 0) return;
+  uint32_t *st = state + (int64_t)row * (2 + 2 * P);
+  const uint32_t *hs = hist + (int64_t)row * P * 2048;
+  const int shift = level == 0 ? 21 : level == 1 ? 10 : 0, nb = level == 2 ? 1024 : 2048;
+  const uint32_t remaining = level == 0 ? (uint32_t)r.count : st[1];
+  // thread t owns the bins nb-1-2t and nb-2-2t of the row's histogram (the parts added up)
+  const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+  uint32_t c0 = 0, c1 = 0;
+  if (b0 >= 0)
+    for (int p = 0; p < P; ++p) {
+      c0 += hs[(int64_t)p * 2048 + b0];
+      if (b1 >= 0) c1 += hs[(int64_t)p * 2048 + b1];
+    }
+  uint32_t total;
+  const uint32_t above = block_exclusive_scan(c0 + c1, wave_tot, &total);
+  if (above < remaining && remaining <= above + c0) {
+    found[0] = (uint32_t)b0;
+    found[1] = remaining - above;
+  } else if (above + c0 < remaining && remaining <= above + c0 + c1) {
+    found[0] = (uint32_t)b1;
+    found[1] = remaining - above - c0;
+  }
+  __syncthreads();
+  const int digit = (int)found[0];
+  // per part: keys above the extended prefix (one wavefront per part), keys equal to it
+  for (int p = wave; p < P; p += kSelWaves) {
+    uint32_t gt = 0;
+    for (int b = digit + 1 + lane; b < nb; b += 64) gt += hs[(int64_t)p * 2048 + b];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) gt += __shfl_down(gt, off, 64);
+    if (lane == 0) {
+      st[2 + p] = (level == 0 ? 0u : st[2 + p]) + gt;
+      st[2 + P + p] = hs[(int64_t)p * 2048 + digit];
+    }
+  }
+  if (tid == 0) {
+    st[0] = (level == 0 ? 0u : st[0]) | ((uint32_t)digit << shift);
+    st[1] = found[1];
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void msel_emit_kernel(Dims d, SeqTab t, const float *__restrict__ pooled,
+                                                                int P, int part_len,
+                                                                const uint32_t *__restrict__ state,
+                                                                int32_t *__restrict__ idx) {
+  __shared__ SelShared sh;
+  const int row = blockIdx.x / P, part = blockIdx.x % P;
+  const RowRef r = row_of(d, t, row, pooled, idx);
+  if (part == 0)
+    for (int x = threadIdx.x; x < d.w; x += kSelThreads) r.out[r.count + x] = r.m + x;   // window, last
+  const int start = part * part_len;
+  const int len = min(part_len, r.m - start);
+  if (r.count <= 0 || len <= 0) return;
+  const uint32_t *st = state + (int64_t)row * (2 + 2 * P);
+  uint32_t gt0 = 0, eq0 = 0;
+  for (int q = 0; q < part; ++q) { gt0 += st[2 + q]; eq0 += st[2 + P + q]; }
+  const float *x = r.x + start;
+  emit_selected(x, len, split_row(x, len), st[0], st[1], r.out, sh, gt0, eq0, start);
 }
 
 // ----------------------------------------------------------------------------------
@@ -657,10 +781,22 @@ hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_
   return hipGetLastError();
 }
 
-hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st) {
+hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, uint32_t *hist, uint32_t *state,
+                         hipStream_t st) {
   const Dims &d = pl.d;
-  const int64_t blocks = (int64_t)d.L * d.S * d.Hkv;
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)blocks), dim3(kSelThreads), 0, st, d, pl.t, pooled, idx);
+  const int64_t rows = (int64_t)d.L * d.S * d.Hkv;
+  if (pl.sel_parts > 1 && hist != nullptr && state != nullptr) {
+    const int P = pl.sel_parts;
+    const dim3 wide((unsigned)(rows * P)), one((unsigned)rows), block(kSelThreads);
+    for (int level = 0; level < 3; ++level) {
+      hipLaunchKernelGGL(msel_hist_kernel, wide, block, 0, st, d, pl.t, pooled, level, P, pl.sel_part_len,
+                         state, hist);
+      hipLaunchKernelGGL(msel_decide_kernel, one, block, 0, st, d, pl.t, level, P, state, hist);
+    }
+    hipLaunchKernelGGL(msel_emit_kernel, wide, block, 0, st, d, pl.t, pooled, P, pl.sel_part_len, state, idx);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, st, d, pl.t, pooled, idx);
   return hipGetLastError();
 }
 

@@ -56,6 +56,9 @@ struct Plan {
   // workspace carve-up (byte offsets, 256-aligned)
   size_t off_part, off_lse, off_planes, off_pooled, off_pooled2, off_sel, total;
   size_t off_ada_hist, off_ada_state, total_ada;   // extra scratch of the shared-budget selection
+  // selection of long rows in calls with few rows: parts per row (1: not split), keys per part, scratch
+  int32_t sel_parts, sel_part_len;
+  size_t off_sel_hist, off_sel_state;
 };
 
 inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -93,7 +96,10 @@ hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *ra
 // max-pool (kernel pool_k, clipped to [0, n_in - n_window)) of one row of n_in scores
 hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_window, int32_t pool_k,
                            hipStream_t st);
-hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, hipStream_t st);
+// hist / state: scratch of the split-row path (off_sel_hist, off_sel_state); with either null, or when
+// the plan does not split rows (sel_parts == 1), every row is ranked by one workgroup.
+hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, uint32_t *hist, uint32_t *state,
+                         hipStream_t st);
 // Shared layer budget: head offsets from a layer-wide threshold, then per-head selection.
 // hist: L*S*Hkv*2048 uint32, state: L*S*(2 + 3*Hkv) uint32 of scratch.
 hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *pooled, int32_t *idx,

@@ -819,13 +819,48 @@ def test_select_on_a_three_million_key_row(S):
         name="long_row", n_layers=1, n_q_heads=2, n_kv_heads=2, head_dim=64, seq_lens=(n,),
         n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
     p = make_params(S, w)
-    idx = torch.full((1, 2 * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
-    S.speckv_select(p, torch.from_numpy(rows.reshape(1, -1)).cuda(), idx)
-    torch.cuda.synchronize()
-    got = idx.cpu().numpy().reshape(2, -1)
-    for g in range(2):
-        want = orc.keep_indices(rows[g, :n - n_window].astype(np.float64), n, n_window, c_max)
-        assert np.array_equal(got[g], want), g
+    pooled = torch.from_numpy(rows.reshape(1, -1)).cuda()
+    want = [orc.keep_indices(rows[g, :n - n_window].astype(np.float64), n, n_window, c_max) for g in range(2)]
+    # without a workspace one workgroup ranks each row; with it the rows are split over many
+    for ws in (None, alloc_ws(S, p)):
+        idx = torch.full((1, 2 * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
+        S.speckv_select(p, pooled, idx, ws)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy().reshape(2, -1)
+        for g in range(2):
+            assert np.array_equal(got[g], want[g]), (g, ws is None)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_split_row_selection_ragged(S, seed):
+    """Few long ragged rows (split over workgroups, parts past a short row's end are empty) with
+    heavy ties, against the oracle and against the one-workgroup path."""
+    rng = np.random.default_rng(3000 + seed)
+    n_window = int(rng.choice([0, 3, 64]))
+    lens = (int(rng.integers(262144 + 70, 600000)), int(rng.integers(max(1, n_window), 5000)), 300001)
+    H, L = 2, 1
+    c_max = int(rng.choice([1, 4096, 250000]))
+    w = workloads.SpecKVWorkload(
+        name="split", n_layers=L, n_q_heads=H, n_kv_heads=H, head_dim=64, seq_lens=lens,
+        n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+    p = make_params(S, w)
+    T = w.total_tokens
+    levels = int(rng.choice([4, 1000, 10 ** 7]))
+    base = (rng.integers(0, levels, size=(L, H * T)).astype(np.float32) - levels // 5) / np.float32(levels)
+    pooled = torch.from_numpy(base).cuda()
+    outs = []
+    for ws in (None, alloc_ws(S, p)):
+        idx = torch.full((L, H * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
+        S.speckv_select(p, pooled, idx, ws)
+        torch.cuda.synchronize()
+        outs.append(idx.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+    for s in range(len(lens)):
+        rows = split_scores(w, base, 0, s)
+        got = split_keep(w, outs[1], 0, s, c_max)
+        for g in range(H):
+            want = orc.keep_indices(rows[g, :lens[s] - n_window].astype(np.float64), lens[s], n_window, c_max)
+            assert np.array_equal(got[g], want), (seed, s, g)
 
 
 def test_two_streams_with_their_own_workspaces(S):
