@@ -119,6 +119,14 @@ int64_t speckv_total_keep(const speckv_params *p);
  * the parameters are invalid. */
 size_t speckv_workspace_bytes(const speckv_params *p);
 
+/* Launch plan the host derives for these parameters, for diagnostics and tests (no GPU needed):
+ * info[0] waves per scoring workgroup, [1] 32-row blocks per wave, [2] row super-blocks per KV group,
+ * [3] keys per chunk of the scoring sweeps, [4] unmasked chunks over all sequences, [5] keys per LDS
+ * tile, [6] parts a row is split into for selection (1: one workgroup per row), [7] keys per such
+ * part.  Returns SPECKV_OK or the reason the parameters are rejected. */
+#define SPECKV_PLAN_INFO_WORDS 8
+speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_INFO_WORDS]);
+
 /* Importance scores (Eq. 1; Alg. 1 CrossAttention, reduce and pooling steps).
  * For every (layer, sequence, KV head): softmax over the visible prompt keys of
  * sm_scale*q.k for each observation row of each query head of the group, summed over

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     n_keep,
+    plan_info,
     specpc_compress_prompt,
     specpc_compress_workspace_bytes,
     specpc_select_tokens,

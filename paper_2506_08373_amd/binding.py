@@ -47,7 +47,7 @@ EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv
            "speckv_compress_events", "speckv_score_lse", "speckv_compress_lse",
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
            "specpc_compress_prompt", "speckv_ada_workspace_bytes", "speckv_select_ada",
-           "speckv_compact_ada", "speckv_compress_ada")
+           "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info")
 
 
 def library_path() -> str:
@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_compress_events.restype = ctypes.c_int
     lib.speckv_compress_events.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp,
                                            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
+    lib.speckv_plan_info.restype = ctypes.c_int
+    lib.speckv_plan_info.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     lib.speckv_ada_workspace_bytes.restype = ctypes.c_size_t
     lib.speckv_ada_workspace_bytes.argtypes = [P]
     lib.speckv_select_ada.restype = ctypes.c_int
@@ -244,6 +246,15 @@ def speckv_compress(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace) -> N
                                           _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
                                           _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
                                           wp, wb, _stream()), "speckv_compress")
+
+
+def plan_info(p: SpecKVParams) -> dict:
+    """The host's launch plan for these parameters (diagnostics; needs no GPU)."""
+    out = (ctypes.c_int64 * 8)()
+    _check(load_library().speckv_plan_info(p.ref(), out), "speckv_plan_info")
+    keys = ("waves", "blocks_per_wave", "row_super_blocks", "chunk_keys", "n_chunks", "tile_keys",
+            "select_parts", "select_part_keys")
+    return dict(zip(keys, (int(x) for x in out)))
 
 
 def ada_workspace_bytes(p: SpecKVParams) -> int:

@@ -220,6 +220,18 @@ int64_t speckv_total_keep(const speckv_params *p) {
   return pl.d.KT;
 }
 
+speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_INFO_WORDS]) {
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (info == nullptr) return SPECKV_ERR_INVALID_ARG;
+  const int rowb = pl.d.D * pl.d.elt;
+  info[0] = pl.g.NW; info[1] = pl.g.MB; info[2] = pl.g.RS; info[3] = pl.g.KC; info[4] = pl.g.n_fast_chunks;
+  info[5] = rowb <= 128 ? 256 : rowb <= 256 ? 128 : 64;
+  info[6] = pl.sel_parts; info[7] = pl.sel_part_len;
+  return SPECKV_OK;
+}
+
 size_t speckv_workspace_bytes(const speckv_params *p) {
   Plan pl;
   if (build_plan(p, &pl, false, 0) != SPECKV_OK) return 0;

@@ -137,3 +137,70 @@ def test_bench_refuses_more_than_one_gpu(repo_root):
     r = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+# --------------------------------------------------------------------------- #
+# The host's launch plan (no GPU needed)
+# --------------------------------------------------------------------------- #
+def test_plan_of_the_benchmark_configurations(lib):
+    import workloads
+    def plan(w):
+        return S.plan_info(S.SpecKVParams(
+            n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+            seq_lens=list(w.seq_lens), n_window=w.n_window, n_lookahead=w.n_lookahead, pool_k=w.pool_k,
+            c_max=w.c_max, sm_scale=w.sm_scale, dtype=w.torch_dtype))
+    c3 = plan(workloads.llama8b_full_128k())
+    # 512 rows per KV group: 8 waves x 2 blocks, one super-block; 4 equal chunks per (layer, head)
+    # = 1024 identical workgroups = 4 whole rounds on 256 CUs
+    assert (c3["waves"], c3["blocks_per_wave"], c3["row_super_blocks"]) == (8, 2, 1)
+    assert c3["chunk_keys"] == 32768 and c3["n_chunks"] == 4 and c3["tile_keys"] == 128
+    assert c3["select_parts"] == 1
+    c4 = plan(workloads.ragged_batch())
+    # G = 7: two super-blocks; ragged lengths: chunks shortened to balance the last round
+    assert c4["row_super_blocks"] == 2 and c4["chunk_keys"] == 8192
+    c5 = plan(workloads.specpc_draft())
+    assert c5["tile_keys"] == 256 and (c5["waves"], c5["blocks_per_wave"]) == (8, 1)
+    tiny = plan(workloads.tiny_fp32())
+    assert (tiny["waves"], tiny["blocks_per_wave"]) == (4, 1) and tiny["tile_keys"] == 128
+
+
+def test_plan_invariants_over_random_shapes(lib):
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        G = int(rng.choice([1, 2, 4, 5, 7, 8, 16]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        d = int(rng.choice([64, 128]))
+        dt = [torch.bfloat16, torch.float16, torch.float32][int(rng.integers(0, 3))]
+        w_ = int(rng.choice([0, 16, 64]))
+        a_ = int(rng.choice([1, 16, 64, 200]))
+        n_seqs = int(rng.choice([1, 1, 3, 16]))
+        lens = [int(x) for x in rng.integers(max(1, w_), int(rng.choice([2000, 70000, 1200000])), size=n_seqs)]
+        L = int(rng.choice([1, 2, 32]))
+        if sum(lens) * L * Hkv > 1 << 31:
+            continue
+        p = S.SpecKVParams(n_layers=L, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_lens=lens,
+                           n_window=w_, n_lookahead=a_, pool_k=7, c_max=1024, sm_scale=0.1, dtype=dt)
+        out = (ctypes.c_int64 * 8)()
+        st = lib.speckv_plan_info(p.ref(), out)
+        if st == -2:
+            continue                                           # outside the supported envelope
+        assert st == 0
+        info = S.plan_info(p)
+        tile, kc = info["tile_keys"], info["chunk_keys"]
+        assert kc % 256 == 0 and kc % tile == 0 and kc >= 512
+        rows_per_wg = info["waves"] * info["blocks_per_wave"] * 32
+        rp = (w_ + a_ + 31) // 32 * 32
+        assert info["row_super_blocks"] * rows_per_wg >= G * min(rp, rows_per_wg) or rp > rows_per_wg
+        # the unmasked chunks cover exactly the whole tiles visible to every row
+        want_chunks = 0
+        for n in lens:
+            visible = min(n, n - w_ + 1)
+            want_chunks += -(-(visible // tile * tile) // kc)
+        assert info["n_chunks"] == want_chunks
+        # rows are split for selection only when they are long and few
+        rows = L * n_seqs * Hkv
+        if info["select_parts"] > 1:
+            assert max(lens) - w_ >= 1 << 18 and rows * info["select_parts"] <= 512 + rows
+            assert info["select_parts"] * info["select_part_keys"] >= max(lens) - w_
+        assert S.workspace_bytes(p) > 0
