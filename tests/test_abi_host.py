@@ -204,3 +204,21 @@ def test_plan_invariants_over_random_shapes(lib):
             assert max(lens) - w_ >= 1 << 18 and rows * info["select_parts"] <= 512 + rows
             assert info["select_parts"] * info["select_part_keys"] >= max(lens) - w_
         assert S.workspace_bytes(p) > 0
+
+
+def test_plain_c_caller(lib, repo_root, tmp_path):
+    """The header and the library from a C99 program (host-side entry points only)."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    pkg = os.path.join(repo_root, "paper_2506_08373_amd")
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.run([cc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(repo_root, "include"),
+                    os.path.join(repo_root, "tests", "c_abi_check.c"), "-o", exe,
+                    "-L", pkg, "-lspeckv", "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib",
+                    "-L", "/opt/rocm/lib", "-lamdhip64"], check=True, capture_output=True, text=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert "workspace" in r.stdout
