@@ -901,3 +901,16 @@ def test_half_precision_inputs(S, head_dim, group):
         n_window=16, n_lookahead=24, pool_k=7, c_max=200, dtype="f16", sm_scale=1.0 / math.sqrt(head_dim),
         n_planted=4, channel_scale=(0.5, 4.0), seed=51)
     check_full_path(S, w)
+
+
+def test_sharp_softmax_large_logits(S):
+    """Logits with a standard deviation of tens of nats (max far above 100): rows are nearly one-hot,
+    most probabilities underflow; no overflow, no NaN, and the scores still match the oracle."""
+    w = workloads.SpecKVWorkload(
+        name="sharp", n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_lens=(3000, 1500),
+        n_window=32, n_lookahead=32, pool_k=7, c_max=300, dtype="bf16", sm_scale=1.0 / math.sqrt(128.0),
+        q_gain=8.0, n_planted=4, channel_scale=(0.5, 4.0), seed=61)
+    t = workloads.generate(w)
+    logits = (t["q"][0, 0, :, 0].float() @ t["k"][0, :3000, 0].float().T) * w.sm_scale
+    assert float(logits.std()) > 20 and float(logits.max()) > 100        # the case is what it claims to be
+    check_full_path(S, w)
