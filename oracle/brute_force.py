@@ -135,3 +135,32 @@ def speckv_layer(q, k, v, n_window: int, pool_k: int, c_max: int, sm_scale: floa
     k_out = [[list(k[j][g]) for j in idx[g]] for g in range(Hkv)]
     v_out = [[list(v[j][g]) for j in idx[g]] for g in range(Hkv)]
     return {"raw": raw, "pooled": pooled, "idx": idx, "k_out": k_out, "v_out": v_out}
+
+
+def compact_ragged(x, idx: Sequence[Sequence[int]]):
+    """x[j][g][c], idx[g] of any length -> rows x[idx[g][r]][g] of head 0, 1, ... one after another
+    (Alg. 1 last step, with a different number of kept rows per head)."""
+    rows = []
+    for g in range(len(idx)):
+        for j in idx[g]:
+            rows.append([float(c) for c in x[j][g]])
+    return rows
+
+
+def speckv_layer_ada(q, k, v, n_window: int, pool_k: int, c_max: int, floor: int, sm_scale: float,
+                     reduce: str = "sum", pool: str = "max"):
+    """One (sequence, layer) with the layer's budget shared across its KV heads, loops only:
+    scores -> pooled -> per-head counts (ada_head_counts) -> each head's best n_h candidates
+    ascending, then the window -> head offsets -> gathered K and V rows."""
+    n, Hkv = len(k), len(k[0])
+    m = n - n_window
+    raw = raw_scores(q, k, n_window, sm_scale, reduce)
+    pool_fn = max_pool if pool == "max" else avg_pool
+    pooled = [pool_fn(raw[g][:m], pool_k) for g in range(Hkv)]
+    counts = ada_head_counts(pooled, min(c_max, m), floor)
+    idx = [select_top(pooled[g], counts[g]) + list(range(m, n)) for g in range(Hkv)]
+    head_off = [0]
+    for g in range(Hkv):
+        head_off.append(head_off[-1] + len(idx[g]))
+    return {"raw": raw, "pooled": pooled, "idx": idx, "head_off": head_off,
+            "k_out": compact_ragged(k, idx), "v_out": compact_ragged(v, idx)}

@@ -125,16 +125,19 @@ def test_llama8b_full_stack_128k(S):
     w = workloads.llama8b_full_128k()
     data, p, idx, k_out, v_out, pooled = run_workload(S, w)
     check_structure_everywhere(w, data, idx, k_out, v_out)
-    check_sampled_heads(w, data, idx, pooled, [(0, 0, 0), (15, 0, 5), (31, 0, 7)])
+    # every KV head of the first, a middle and the last layer against the oracle
+    check_sampled_heads(w, data, idx, pooled, [(layer, 0, g) for layer in (0, 15, 31) for g in range(w.n_kv_heads)])
 
 
 def test_ragged_batch_full(S):
     w = workloads.ragged_batch()
     data, p, idx, k_out, v_out, pooled = run_workload(S, w)
     check_structure_everywhere(w, data, idx, k_out, v_out)
+    # one head of every sequence (layers and heads rotate), plus the two extreme lengths on other layers
     longest = int(np.argmax(w.seq_lens))
     shortest = int(np.argmin(w.seq_lens))
-    check_sampled_heads(w, data, idx, pooled, [(0, shortest, 0), (27, longest, 3), (13, 4, 2)])
+    samples = [((5 * s) % w.n_layers, s, s % w.n_kv_heads) for s in range(w.n_seqs)]
+    check_sampled_heads(w, data, idx, pooled, samples + [(0, shortest, 0), (27, longest, 3)])
 
 
 def test_specpc_full(S):

@@ -560,19 +560,47 @@ def test_ada_tie_rule_prefers_smaller_head_then_index():
     assert idx[0].tolist() == [0, 1, 2] and idx[1].tolist() == [2]
 
 
-def test_ada_layer_end_to_end_against_brute_force():
+def _ada_tiny():
     w = workloads.SpecKVWorkload(name="ada_tiny", n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=8,
                                  seq_lens=(40,), n_window=4, n_lookahead=3, pool_k=3, c_max=6,
                                  dtype="f32", sm_scale=0.5, n_planted=2)
     t = workloads.generate(w)
     q, k, v = (workloads.to_float64(t[x][0]) for x in ("q", "k", "v"))
-    q = q[0]
-    out = orc.speckv_layer_ada(q, k, v, 4, 3, 6, 2, 0.5)
-    ref = bf.speckv_layer(q.tolist(), k.tolist(), v.tolist(), 4, 3, 6, 0.5)
-    counts = bf.ada_head_counts(ref["pooled"], 6, 2)
-    assert [len(i) - 4 for i in out["idx"]] == counts
-    assert out["head_off"].tolist() == [0, counts[0] + 4, counts[0] + counts[1] + 8]
-    for g in range(2):
-        assert out["idx"][g][:-4].tolist() == bf.select_top(ref["pooled"][g], counts[g])
-    rows = np.concatenate([k[out["idx"][g], g, :] for g in range(2)])
-    assert np.array_equal(out["k_out"], rows)
+    return q[0], k, v
+
+
+@pytest.mark.parametrize("floor", [0, 2, 6, 9])
+def test_ada_layer_end_to_end_against_brute_force(floor):
+    """speckv_layer_ada and compact_ragged against the loops-only brute force of the same path:
+    indices, head offsets and the gathered K and V rows."""
+    q, k, v = _ada_tiny()
+    out = orc.speckv_layer_ada(q, k, v, 4, 3, 6, floor, 0.5)
+    ref = bf.speckv_layer_ada(q.tolist(), k.tolist(), v.tolist(), 4, 3, 6, floor, 0.5)
+    assert [i.tolist() for i in out["idx"]] == ref["idx"]
+    assert out["head_off"].tolist() == ref["head_off"]
+    assert out["head_off"][-1] == 2 * (6 + 4)                      # the layer total never moves
+    assert out["k_out"].shape == (ref["head_off"][-1], 8)
+    assert out["k_out"].tolist() == ref["k_out"]
+    assert out["v_out"].tolist() == ref["v_out"]
+    # K and V differ, so a swap of the two tensors could not pass
+    assert out["k_out"].tolist() != out["v_out"].tolist()
+
+
+def test_compact_ragged_against_hand_written_rows():
+    """Two heads with different counts on a tensor whose entries name their own position."""
+    n, H, d = 6, 2, 3
+    x = np.array([[[100 * j + 10 * g + c for c in range(d)] for g in range(H)] for j in range(n)], dtype=np.float64)
+    idx = [np.array([4, 1]), np.array([0, 2, 5])]
+    want = [[400, 401, 402], [100, 101, 102], [10, 11, 12], [210, 211, 212], [510, 511, 512]]
+    assert orc.compact_ragged(x, idx).tolist() == want
+    assert bf.compact_ragged(x.tolist(), [i.tolist() for i in idx]) == want
+
+
+def test_planted_wrong_head_in_the_ragged_gather_is_caught():
+    """A gather that reads every row from head 0 (a dropped head index) must fail the pin."""
+    q, k, v = _ada_tiny()
+    ref = bf.speckv_layer_ada(q.tolist(), k.tolist(), v.tolist(), 4, 3, 6, 2, 0.5)
+    wrong = np.concatenate([k[np.asarray(ref["idx"][g]), 0, :] for g in range(2)], axis=0)
+    assert wrong.tolist() != ref["k_out"]
+    shifted = np.concatenate([k[np.asarray(ref["idx"][g]), (g + 1) % 2, :] for g in range(2)], axis=0)
+    assert shifted.tolist() != ref["k_out"]
