@@ -12,7 +12,8 @@
  * ---------------------------------------
  *  - All data pointers are DEVICE pointers owned by the caller unless a comment says
  *    HOST.  The library allocates no device memory and keeps no state between calls;
- *    scratch comes from the caller's workspace (size from *_workspace_bytes).
+ *    scratch comes from the caller's workspace (size from *_workspace_bytes).  The one
+ *    exception is speckv_compress_static, which uses a fixed array inside the library.
  *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *    stream) and the call returns without synchronising.  Outputs are valid once the
  *    stream reaches that point.  Inputs are never modified.
@@ -167,6 +168,22 @@ speckv_status speckv_compact(const speckv_params *p, const void *k, const void *
 speckv_status speckv_compress(const speckv_params *p, const void *q, const void *k,
                               const void *v, int32_t *idx, void *k_out, void *v_out,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* speckv_compress for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and bit-identical
+ * results; the scratch is a fixed array of SPECKV_STATIC_SCRATCH_BYTES inside the library's device
+ * code (one copy per GPU, held until the process ends; its address is looked up on the first call
+ * on each device).  The call allocates nothing and frees nothing.  Parameters whose
+ * speckv_workspace_bytes exceeds SPECKV_STATIC_SCRATCH_BYTES are rejected with
+ * SPECKV_ERR_WORKSPACE before anything is launched (32 MiB covers one layer of 8 KV heads at
+ * 256K tokens, or a few layers of shorter prompts).  Every call on a GPU shares that GPU's array:
+ * calls that overlap on one GPU (two streams, two threads) race and must be serialised by the
+ * caller.  The array keeps the previous call's contents; the kernels never read what they have
+ * not written in the same call, so nothing needs clearing. */
+#define SPECKV_STATIC_SCRATCH_BYTES (32u << 20)
+speckv_status speckv_compress_static(const speckv_params *p, const void *q, const void *k,
+                                     const void *v, int32_t *idx, void *k_out, void *v_out,
+                                     void *stream);
 
 /* speckv_compress with caller-supplied row normalisers (see speckv_score_lse). */
 speckv_status speckv_compress_lse(const speckv_params *p, const void *q, const void *k,

@@ -24,6 +24,8 @@ from .binding import (  # noqa: F401
     speckv_compress,
     speckv_compress_events,
     speckv_compress_lse,
+    speckv_compress_static,
+    STATIC_SCRATCH_BYTES,
     speckv_score_lse,
     N_STAGE_EVENTS,
     STAGE_NAMES,

@@ -47,7 +47,7 @@ EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv
            "speckv_compress_events", "speckv_score_lse", "speckv_compress_lse",
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
            "specpc_compress_prompt", "speckv_ada_workspace_bytes", "speckv_select_ada",
-           "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info")
+           "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info", "speckv_compress_static")
 
 
 def library_path() -> str:
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_compact.argtypes = [P, vp, vp, i32p, vp, vp, vp]
     lib.speckv_compress.restype = ctypes.c_int
     lib.speckv_compress.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.speckv_compress_static.restype = ctypes.c_int
+    lib.speckv_compress_static.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp]
     lib.speckv_compress_events.restype = ctypes.c_int
     lib.speckv_compress_events.argtypes = [P, vp, vp, vp, i32p, vp, vp, vp, ctypes.c_size_t, vp,
                                            ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
@@ -246,6 +248,17 @@ def speckv_compress(p: SpecKVParams, q, k, v, idx, k_out, v_out, workspace) -> N
                                           _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
                                           _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
                                           wp, wb, _stream()), "speckv_compress")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def speckv_compress_static(p: SpecKVParams, q, k, v, idx, k_out, v_out) -> None:
+    """speckv_compress on the library's own fixed scratch: no workspace, no allocation."""
+    _check(load_library().speckv_compress_static(p.ref(), _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+                                                 _ptr(v, p.torch_dtype), _ptr(idx, torch.int32),
+                                                 _ptr(k_out, p.torch_dtype), _ptr(v_out, p.torch_dtype),
+                                                 _stream()), "speckv_compress_static")
 
 
 def plan_info(p: SpecKVParams) -> dict:

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "speckv_internal.h"
 
@@ -190,6 +191,29 @@ speckv_status check_ws(const Plan &pl, const void *ws, size_t ws_bytes) {
 
 speckv_status from_hip(hipError_t e) { return e == hipSuccess ? SPECKV_OK : SPECKV_ERR_RUNTIME; }
 
+// Scratch of speckv_compress_static: one array per GPU, part of the library's code object, so a
+// caller that may not allocate (HIP graph capture, a serving loop) still has a workspace.  The
+// name below is only a host-side handle; the device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what the kernels and every other host use get.
+static __device__ __align__(256) unsigned char scratch[SPECKV_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+speckv_status static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPECKV_ERR_RUNTIME;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return SPECKV_ERR_RUNTIME;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SPECKV_OK;
+}
+
 }  // namespace
 }  // namespace speckv
 
@@ -339,6 +363,17 @@ speckv_status speckv_compress(const speckv_params *p, const void *q, const void 
                               int32_t *idx, void *k_out, void *v_out, void *workspace,
                               size_t workspace_bytes, void *stream) {
   return compress_impl(p, q, k, v, idx, k_out, v_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+speckv_status speckv_compress_static(const speckv_params *p, const void *q, const void *k, const void *v,
+                                     int32_t *idx, void *k_out, void *v_out, void *stream) {
+  Plan pl;
+  speckv_status st = build_plan(p, &pl, false, 0);
+  if (st != SPECKV_OK) return st;
+  if (pl.total > (size_t)SPECKV_STATIC_SCRATCH_BYTES) return SPECKV_ERR_WORKSPACE;   // problem too large for the fixed scratch
+  void *ws = nullptr;
+  if ((st = static_scratch(&ws)) != SPECKV_OK) return st;
+  return compress_impl(p, q, k, v, idx, k_out, v_out, ws, (size_t)SPECKV_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 speckv_status speckv_compress_lse(const speckv_params *p, const void *q, const void *k, const void *v,
