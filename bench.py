@@ -1,20 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the SpecKV hot path on one MI355X.
 
-A step is one `speckv_compress` call over the whole synthetic workload (all layers):
-scoring pass 1, row-statistics merge, scoring pass 2, pooling, selection, compaction.
-Inputs are generated on the GPU and resident in HBM before the timed region.  Prints ONE
-JSON line: whole-job throughput in prompt keys scored + compacted per second
-(n_in x layers x kv_heads / time), a roofline object for the dominant kernel (timed live
-with HIP events recorded on the launch stream inside the timed steps) and the CPU oracle
-timed on a bounded sample of the same workload.
+A step is one pass of the whole hot path over the synthetic workload: for the SpecKV
+workloads (c1-c4) one `speckv_compress` call over all layers (scoring pass 1, row-statistics
+merge, scoring pass 2, pooling, selection, compaction); for the prompt-token workload (c5) one
+`specpc_select_tokens` call (the two scoring sweeps over all layers, the cross-layer reduction
+and pooling, top-k selection, neighbour expansion and id gather).  Inputs are generated on the
+GPU and resident in HBM before the timed region.  Prints ONE JSON line: whole-job throughput in
+prompt keys scored + compacted per second (n_in x layers x kv_heads / time), a roofline object
+for the dominant kernel (timed live with HIP events recorded on the launch stream inside the
+timed steps), the single-sweep variant (row normalisers supplied by the caller) and the CPU
+oracle timed on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5]
+                    [--layers L] [--reduce sum|max]
 """
 from __future__ import annotations
 
 import argparse
 import ctypes
+import dataclasses
 import json
 import os
 import re
@@ -29,8 +34,14 @@ sys.path.insert(0, ROOT)
 
 import workloads  # noqa: E402
 
-PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
-PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# MI355X published peaks
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+# Plain fp32 vector arithmetic without packed operations (this build disables them):
+# 256 CUs x 64 lanes x 2.4 GHz x 2 flops per fused multiply-add.
+PEAK_ALU_TFLOPS = 256 * 64 * 2.4e9 * 2 / 1e12
+# vector work per score element and sweep: one fused multiply-add, one exp2, one add
+ALU_FLOPS_PER_SCORE = 4.0
 
 
 def _hip_runtime() -> ctypes.CDLL:
@@ -53,16 +64,64 @@ def _hip_runtime() -> ctypes.CDLL:
     return hip
 
 
-def _traffic_from_profile(kernel: str, workload: str):
+def _traffic_from_profile(stage: str, tag: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if any."""
-    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % workload)
+    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % tag)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
-        m = re.match(r"\s*%s\s+hbm_bytes_per_launch=([0-9.eE+]+)" % re.escape(kernel), line)
+        m = re.match(r"\s*%s\s+hbm_bytes_per_launch=([0-9.eE+]+)" % re.escape(stage), line)
         if m:
-            return float(m.group(1))
-    return None
+            return float(m.group(1)), "profiles/pmc_traffic_%s.txt" % tag
+    return None, None
+
+
+def _scoring_kernel_symbol(S, p, w, stage: str) -> str:
+    """Name of the unmasked scoring kernel of this stage as a rocprofv3 kernel trace shows it."""
+    info = S.plan_info(p)
+    dt = {"bf16": 0, "f32": 1, "f16": 2}[w.dtype]
+    npass = 1 if stage == "score_pass1" else 2
+    red = info["reduce_max"] if npass == 2 else 0
+    if info["q_stationary"]:
+        return "score_qs_kernel<%d, %d, %d, %d>" % (dt, w.head_dim, npass, red)
+    fn = "score_kernel_rows" if (npass == 1 and info["waves"] == 8) else "score_kernel_cols"
+    return "%s<%d, %d, %d, %d, %d, %d, false>" % (fn, dt, w.head_dim, info["blocks_per_wave"], info["waves"],
+                                                  npass, red)
+
+
+def _make_events(hip, n_sets: int, ne: int):
+    sets = []
+    for _ in range(n_sets):
+        arr = (ctypes.c_void_p * ne)()
+        for i in range(ne):
+            h = ctypes.c_void_p()
+            if hip.hipEventCreate(ctypes.byref(h)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            arr[i] = h
+        sets.append(arr)
+    return sets
+
+
+def _stage_means(hip, ev_sets, ne: int) -> np.ndarray:
+    ms_all = np.zeros((len(ev_sets), ne - 1))
+    for step, arr in enumerate(ev_sets):
+        for i in range(ne - 1):
+            ms = ctypes.c_float()
+            if hip.hipEventElapsedTime(ctypes.byref(ms), arr[i], arr[i + 1]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            ms_all[step, i] = ms.value
+    for arr in ev_sets:
+        for i in range(ne):
+            hip.hipEventDestroy(arr[i])
+    return ms_all.mean(axis=0)
+
+
+def _blas_threads() -> int:
+    try:
+        from threadpoolctl import threadpool_info
+        return max([x.get("num_threads", 1) for x in threadpool_info()] or [1])
+    except Exception:
+        return 1
 
 
 def main() -> int:
@@ -70,10 +129,16 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's number of layers")
+    ap.add_argument("--reduce", default="sum", choices=["sum", "max"],
+                    help="reduction over the observation rows of a head (max: the listing's MaxReduce)")
+    ap.add_argument("--paper-setting", action="store_true",
+                    help="the hyper-parameter table's SpecKV column: max reduction, max pooling k = 7, "
+                         "n_window = 32 (the lookahead rows grow to keep 128 rows), budget C_max - n_window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--lse-variant", action="store_true",
-                    help="also time the single-sweep variant with caller-supplied row normalisers")
+    ap.add_argument("--no-lse-variant", action="store_true",
+                    help="skip the single-sweep figure (row normalisers supplied by the caller)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 "
                          "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
@@ -91,32 +156,62 @@ def main() -> int:
     S.load_library()
     torch.cuda.set_device(0)
     w = workloads.PRESETS[args.workload]()
+    if args.layers > 0:
+        w = dataclasses.replace(w, n_layers=args.layers, name="%s_%dlayers" % (w.name, args.layers))
+    reduce = args.reduce
+    if args.paper_setting:
+        if args.workload == "c5":
+            print("bench.py: --paper-setting applies to the SpecKV workloads c1-c4", file=sys.stderr)
+            return 2
+        rows = w.n_rows
+        w = dataclasses.replace(w, n_window=32, n_lookahead=rows - 32, c_max=max(w.c_max - 32, 0),
+                                name=w.name + "_paper_setting")
+        reduce = "max"
+    specpc = args.workload == "c5"
+    tag = args.workload if (args.layers <= 0 and reduce == "sum" and not args.paper_setting) else None
+
     t0 = time.time()
     data = workloads.generate(w, device="cuda")
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     q, k, v = data["q"], data["k"], data["v"]
+    L, H, d, G = w.n_layers, w.n_kv_heads, w.head_dim, w.group
+    elt = 4 if w.dtype == "f32" else 2
 
     p = S.SpecKVParams.for_tensors(q, k, seq_lens=w.seq_lens, n_window=w.n_window, pool_k=w.pool_k,
-                                   c_max=w.c_max, sm_scale=w.sm_scale)
-    KT = S.total_keep(p)
-    L, H, d = w.n_layers, w.n_kv_heads, w.head_dim
-    idx = torch.empty((L, H * KT), dtype=torch.int32, device="cuda")
-    k_out = torch.empty((L, H * KT, d), dtype=w.torch_dtype, device="cuda")
-    v_out = torch.empty_like(k_out)
-    ws = torch.empty(S.workspace_bytes(p), dtype=torch.uint8, device="cuda")
-
+                                   c_max=w.c_max, sm_scale=w.sm_scale, reduce=reduce)
     hip = _hip_runtime()
     NE = S.N_STAGE_EVENTS
-    ev_sets = []
-    for _ in range(args.steps):
-        arr = (ctypes.c_void_p * NE)()
-        for i in range(NE):
-            h = ctypes.c_void_p()
-            if hip.hipEventCreate(ctypes.byref(h)) != 0:
-                raise RuntimeError("hipEventCreate failed")
-            arr[i] = h
-        ev_sets.append(arr)
+    ev_sets = _make_events(hip, args.steps, NE)
+
+    if specpc:
+        top_k, nb = w.c_max, workloads.SPECPC_NEIGHBORS
+        n = w.seq_lens[0]
+        ids = workloads.generate_token_ids(w, device="cuda")
+        idx_out = torch.empty(n, dtype=torch.int32, device="cuda")
+        ids_out = torch.empty(n, dtype=torch.int32, device="cuda")
+        count = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(S.specpc_workspace_bytes(p, top_k), dtype=torch.uint8, device="cuda")
+        stage_names = S.SPECPC_STAGE_NAMES
+
+        def plain_call():
+            S.specpc_select_tokens(p, top_k, nb, q, k, ids, idx_out, ids_out, count, ws)
+
+        def timed_call(ev):
+            S.specpc_select_tokens_events(p, top_k, nb, q, k, ids, idx_out, ids_out, count, ws, ev)
+    else:
+        KT = S.total_keep(p)
+        idx = torch.empty((L, H * KT), dtype=torch.int32, device="cuda")
+        k_out = torch.empty((L, H * KT, d), dtype=w.torch_dtype, device="cuda")
+        v_out = torch.empty_like(k_out)
+        ws = torch.empty(max(S.workspace_bytes(p), 256), dtype=torch.uint8, device="cuda")
+        stage_names = S.STAGE_NAMES
+
+        def plain_call():
+            S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
+
+        def timed_call(ev):
+            S.speckv_compress_events(p, q, k, v, idx, k_out, v_out, ws, ev)
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -126,48 +221,52 @@ def main() -> int:
         del src, dst
 
     for _ in range(args.warmup):
-        S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
+        plain_call()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for step in range(args.steps):
-        S.speckv_compress_events(p, q, k, v, idx, k_out, v_out, ws, ev_sets[step])
+        timed_call(ev_sets[step])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-
-    stage_ms = np.zeros((args.steps, NE - 1))
-    for step, arr in enumerate(ev_sets):
-        for i in range(NE - 1):
-            ms = ctypes.c_float()
-            if hip.hipEventElapsedTime(ctypes.byref(ms), arr[i], arr[i + 1]) != 0:
-                raise RuntimeError("hipEventElapsedTime failed")
-            stage_ms[step, i] = ms.value
-    for arr in ev_sets:
-        for i in range(NE):
-            hip.hipEventDestroy(arr[i])
-    mean_ms = stage_ms.mean(axis=0)
+    mean_ms = _stage_means(hip, ev_sets, NE)
 
     # algorithmic work per launch
-    qk_flops = 2.0 * w.n_rows * w.n_q_heads * w.total_tokens * d * L        # one Q.K^T over the workload
-    elt = 2 if w.dtype == "bf16" else 4
-    compact_bytes = 2.0 * 2.0 * H * KT * d * elt * L + 4.0 * H * KT * L      # K,V read + write, indices
+    n_scores = float(w.n_rows) * w.n_q_heads * w.total_tokens * L          # score elements of one sweep
+    qk_flops = 2.0 * n_scores * d                                          # one Q.K^T over the workload
+    k_bytes = float(w.total_tokens) * H * d * elt * L                      # K read once
+    peak_mfma = PEAK_MFMA_TFLOPS[w.dtype]
     kernels = {}
-    for name, ms in zip(S.STAGE_NAMES, mean_ms):
+    for name, ms in zip(stage_names, mean_ms):
         entry = {"ms": round(float(ms), 4)}
         if name in ("score_pass1", "score_pass2"):
-            entry.update(bound="mfma", achieved=round(qk_flops / (ms * 1e-3) / 1e12, 2),
-                         peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+            entry.update(bound="mfma", achieved=round(qk_flops / (ms * 1e-3) / 1e12, 2), peak=peak_mfma,
+                         unit="TFLOP/s", kernel=_scoring_kernel_symbol(S, p, w, name),
+                         k_read_GBps=round(k_bytes / (ms * 1e-3) / 1e9, 1),
+                         alu_TFLOPs=round(ALU_FLOPS_PER_SCORE * n_scores / (ms * 1e-3) / 1e12, 2))
         elif name == "compact":
-            entry.update(bound="hbm", achieved=round(compact_bytes / (ms * 1e-3) / 1e9, 1),
-                         peak=PEAK_HBM_GBS, unit="GB/s")
+            KT = S.total_keep(p)
+            compact_bytes = 2.0 * 2.0 * H * KT * d * elt * L + 4.0 * H * KT * L   # K,V read + write, indices
+            entry.update(bound="hbm", achieved=round(compact_bytes / (ms * 1e-3) / 1e9, 1), peak=PEAK_HBM_GBS,
+                         unit="GB/s", kernel="compact_kernel<true>")
         if "achieved" in entry:
             entry["frac"] = round(entry["achieved"] / entry["peak"], 4)
         kernels[name] = entry
-    dominant = max(("score_pass1", "score_pass2"), key=lambda n: kernels[n]["ms"])
-    roofline = {"kernel": dominant, "bound": "mfma", "achieved": kernels[dominant]["achieved"],
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": kernels[dominant]["frac"],
-                "traffic": _traffic_from_profile(dominant, args.workload),
-                "avg_launch_ms": kernels[dominant]["ms"]}
-    k_read_gbs = (w.total_tokens * H * d * elt * L) / (kernels[dominant]["ms"] * 1e-3) / 1e9
+    dominant = max(("score_pass1", "score_pass2"), key=lambda n_: kernels[n_]["ms"])
+    dk = kernels[dominant]
+    traffic, traffic_src = (None, None) if tag is None else _traffic_from_profile(dominant, tag)
+    if d == 64:
+        # at d = 64 a 32x32 score block costs half the matrix time of d = 128 but the same softmax
+        # arithmetic: these sweeps are bound by the vector pipe, priced in plain (unpacked) fp32
+        roofline = {"kernel": dk["kernel"], "stage": dominant, "bound": "alu", "achieved": dk["alu_TFLOPs"],
+                    "peak": round(PEAK_ALU_TFLOPS, 1), "unit": "TFLOP/s",
+                    "frac": round(dk["alu_TFLOPs"] / PEAK_ALU_TFLOPS, 4),
+                    "peak_derivation": "256 CUs x 64 lanes x 2.4 GHz x 2 flops, no packed fp32; 4 flops per "
+                                       "score element and sweep (fma, exp2, add)",
+                    "mfma_frac": dk["frac"], "hbm_frac_k_read": round(dk["k_read_GBps"] / PEAK_HBM_GBS, 4)}
+    else:
+        roofline = {"kernel": dk["kernel"], "stage": dominant, "bound": "mfma", "achieved": dk["achieved"],
+                    "peak": peak_mfma, "unit": "TFLOP/s", "frac": dk["frac"]}
+    roofline.update(traffic=traffic, traffic_source=traffic_src, avg_launch_ms=dk["ms"])
 
     ms_per_step = elapsed / args.steps * 1e3
     value = w.key_units / (elapsed / args.steps)
@@ -175,16 +274,18 @@ def main() -> int:
     # Context figure (not the headline): the same step when the caller already holds the row
     # log-sum-exps (e.g. from the prefill attention kernel) and scoring needs one sweep only.
     lse_variant = None
-    if args.lse_variant:
+    if not args.no_lse_variant and not specpc:
         lse_in = torch.empty((L, w.n_seqs, w.n_rows, w.n_q_heads), dtype=torch.float32, device="cuda")
         cu = w.cu_seqlens
         for layer in range(L):
             for s_ in range(w.n_seqs):
                 kk = k[layer, cu[s_]:cu[s_ + 1]].float()                       # [n, Hkv, d]
-                qq = q[layer, s_].float().view(w.n_rows, H, w.group, d)        # [R, Hkv, G, d]
-                logits = torch.einsum("rhgd,nhd->rhgn", qq, kk) * w.sm_scale   # causal mask ignored: timing only
-                lse_in[layer, s_] = torch.logsumexp(logits, dim=-1).reshape(w.n_rows, w.n_q_heads)
-                del logits, kk, qq
+                qq = q[layer, s_].float().view(w.n_rows, H, G, d)              # [R, Hkv, G, d]
+                for g in range(H):                                             # causal mask ignored: timing only
+                    logits = torch.einsum("rgd,nd->rgn", qq[:, g], kk[:, g]) * w.sm_scale
+                    lse_in[layer, s_, :, g * G:(g + 1) * G] = torch.logsumexp(logits, dim=-1)
+                    del logits
+                del kk, qq
         for _ in range(args.warmup):
             S.speckv_compress_lse(p, q, k, v, lse_in, idx, k_out, v_out, ws)
         torch.cuda.synchronize()
@@ -197,57 +298,71 @@ def main() -> int:
                        "value": round(w.key_units / (el / args.steps), 1), "unit": "keys/s",
                        "note": "speckv_compress_lse: row normalisers supplied by the caller, one sweep over K"}
         del lse_in
-        # restore the headline outputs for the parity check below
-        S.speckv_compress(p, q, k, v, idx, k_out, v_out, ws)
+        plain_call()                        # restore the headline outputs for the parity check below
         torch.cuda.synchronize()
 
     cpu_baseline = None
     parity = None
     if not args.no_cpu_baseline:
         from oracle import speckv_oracle as orc          # CPU baseline leg only
-        try:
-            from threadpoolctl import threadpool_info
-            blas_threads = max([x.get("num_threads", 1) for x in threadpool_info()] or [1])
-        except Exception:
-            blas_threads = 1
         cores = len(os.sched_getaffinity(0))
-        s = 0
+        threads = min(cores, _blas_threads())
         cu = w.cu_seqlens
-        n0 = w.seq_lens[s]
-        keep0 = w.n_keep(s)
-        # bounded sample: about 10 s of oracle time (one 128K layer of the 8B shape takes ~2.5 s)
-        n_sample = max(1, min(L, int(round(4 * (131072 * 8) / (n0 * H)))))
-        layers = sorted(set(int(round(x)) for x in np.linspace(0, L - 1, n_sample)))
-        cpu_s, rows_equal = 0.0, 0
-        for layer in layers:
-            qh = workloads.to_float64(q[layer, s])
-            kh = workloads.to_float64(k[layer, cu[s]:cu[s + 1]])
-            vh = workloads.to_float64(v[layer, cu[s]:cu[s + 1]])
+        if specpc:
+            n = w.seq_lens[0]
+            qh, kh = workloads.to_float64(q[:, 0]), workloads.to_float64(k)
+            ids_h = ids.cpu().numpy()
             t0 = time.perf_counter()
-            ref = orc.speckv_layer(qh, kh, vh, w.n_window, w.pool_k, w.c_max, w.sm_scale)
-            cpu_s += time.perf_counter() - t0
-            got = idx[layer, : H * keep0].reshape(H, keep0).cpu().numpy()
-            rows_equal += int(sum(np.array_equal(got[g], ref["idx"][g]) for g in range(H)))
-        cpu_baseline = {"value": round(len(layers) * n0 * H / cpu_s, 1), "unit": "keys/s",
-                        "cores": min(cores, blas_threads), "kind": "oracle", "seconds": round(cpu_s, 2),
-                        "host_cores_visible": cores,
-                        "sample": "layers %s, sequence %d of %s (all %d KV heads, n_in=%d): %d/%d of a step"
-                                  % (layers, s, w.name, H, n0, len(layers) * n0 * H, w.key_units)}
-        parity = {"sample": "layers %s seq %d" % (layers, s), "index_rows_equal_to_oracle": rows_equal,
-                  "index_rows": H * len(layers)}
+            ref = orc.specpc_select_tokens(qh, kh, ids_h, w.n_window, w.pool_k, top_k, nb, w.sm_scale)
+            cpu_s = time.perf_counter() - t0
+            c = int(count.item())
+            got = idx_out[:c].cpu().numpy().astype(np.int64)
+            cpu_baseline = {"value": round(w.key_units / cpu_s, 1), "unit": "keys/s", "cores": threads,
+                            "kind": "oracle", "seconds": round(cpu_s, 2), "host_cores_visible": cores,
+                            "sample": "the whole call: all %d layers of %s" % (L, w.name)}
+            parity = {"sample": "whole call", "count": c, "count_oracle": int(ref["count"]),
+                      "indices_equal_to_oracle": bool(np.array_equal(got, ref["idx"])),
+                      "indices_in_common": int(np.isin(got, ref["idx"]).sum())}
+        else:
+            s = 0
+            n0, keep0 = w.seq_lens[s], w.n_keep(s)
+            # bounded sample: about 10 s of oracle time = four 128K layers of the 8B shape; the oracle's
+            # cost per layer grows with n_in x query heads x rows x head_dim
+            ref_cost = 131072.0 * 32 * 128 * 128
+            n_sample = max(1, min(L, int(round(4 * ref_cost / (float(n0) * w.n_q_heads * w.n_rows * d)))))
+            layers = sorted(set(int(round(x)) for x in np.linspace(0, L - 1, n_sample)))
+            cpu_s, rows_equal = 0.0, 0
+            for layer in layers:
+                qh = workloads.to_float64(q[layer, s])
+                kh = workloads.to_float64(k[layer, cu[s]:cu[s + 1]])
+                vh = workloads.to_float64(v[layer, cu[s]:cu[s + 1]])
+                t0 = time.perf_counter()
+                ref = orc.speckv_layer(qh, kh, vh, w.n_window, w.pool_k, w.c_max, w.sm_scale, reduce=reduce)
+                cpu_s += time.perf_counter() - t0
+                got = idx[layer, : H * keep0].reshape(H, keep0).cpu().numpy()
+                rows_equal += int(sum(np.array_equal(got[g], ref["idx"][g]) for g in range(H)))
+            cpu_baseline = {"value": round(len(layers) * n0 * H / cpu_s, 1), "unit": "keys/s",
+                            "cores": threads, "kind": "oracle", "seconds": round(cpu_s, 2),
+                            "host_cores_visible": cores,
+                            "sample": "layers %s, sequence %d of %s (all %d KV heads, n_in=%d): %d/%d of a step"
+                                      % (layers, s, w.name, H, n0, len(layers) * n0 * H, w.key_units)}
+            parity = {"sample": "layers %s seq %d" % (layers, s), "index_rows_equal_to_oracle": rows_equal,
+                      "index_rows": H * len(layers)}
 
+    config = {"workload": w.name, "call": "specpc_select_tokens" if specpc else "speckv_compress",
+              "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": H, "head_dim": d,
+              "n_in": list(w.seq_lens), "n_window": w.n_window, "n_lookahead": w.n_lookahead,
+              "pool_k": w.pool_k, "c_max": w.c_max, "reduce": reduce, "parallelism": "single GPU"}
+    if specpc:
+        config.update(top_k=w.c_max, n_neighbor=workloads.SPECPC_NEIGHBORS)
     out = {
         "metric": "prompt keys scored+compacted/sec (n_in x layers x kv_heads)",
         "value": round(value, 1), "unit": "keys/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "n_layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": H,
-                   "head_dim": d, "n_in": list(w.seq_lens), "n_window": w.n_window,
-                   "n_lookahead": w.n_lookahead, "pool_k": w.pool_k, "c_max": w.c_max,
-                   "parallelism": "single GPU"},
+        "config": config,
         "roofline": roofline,
         "kernels": kernels,
-        "k_read_GBps_in_dominant_kernel": round(k_read_gbs, 1),
         "single_sweep_variant": lse_variant,
         "cpu_baseline": cpu_baseline,
         "parity_check": parity,

@@ -18,7 +18,9 @@
  *    stream) and the call returns without synchronising.  Outputs are valid once the
  *    stream reaches that point.  Inputs are never modified.
  *  - The return value is the only error channel.  Arguments are validated on the host
- *    before anything is launched; a failed call has launched nothing.
+ *    before anything is launched: a call that returns INVALID_ARG, UNSUPPORTED or WORKSPACE has
+ *    launched nothing.  SPECKV_ERR_RUNTIME means the HIP runtime refused a launch; kernels of
+ *    the same call that were enqueued before it still run, and the outputs are undefined.
  *  - Element strides are in ELEMENTS of `dtype`; the head dimension is contiguous and
  *    every row (d elements) must start on a 16-byte boundary.
  *  - Readings of the paper fixed by this library: by default the reduction over queries and
@@ -78,8 +80,14 @@ typedef enum { SPECKV_REDUCE_SUM = 0, SPECKV_REDUCE_MAX = 1 } speckv_reduce_op;
  * library padding convention). */
 typedef enum { SPECKV_POOL_MAX = 0, SPECKV_POOL_AVG = 1 } speckv_pool_op;
 
-#define SPECKV_MAX_SEQS 128     /* sequences per call                                        */
-#define SPECKV_MAX_GROUP_ROWS 4096 /* (n_q_heads / n_kv_heads) * R upper bound               */
+/* Limits (a request beyond them returns SPECKV_ERR_UNSUPPORTED):
+ *  - sequences per call: the per-sequence tables travel to the kernels by value in the kernel
+ *    argument block, which bounds their length; batch larger sets over several calls;
+ *  - observation rows of one KV group, (n_q_heads / n_kv_heads) * R: bounds the row-statistics
+ *    workspace per key chunk;
+ *  - n_layers * n_kv_heads * (row super-blocks per group) <= 2^24 and total tokens <= 2^30. */
+#define SPECKV_MAX_SEQS 128
+#define SPECKV_MAX_GROUP_ROWS 4096
 #define SPECKV_MAX_POOL_K 255
 
 /* Problem statement of Alg. 1 (sequence lengths, n_lookahead, C_max, n_window, k) plus
@@ -124,8 +132,10 @@ size_t speckv_workspace_bytes(const speckv_params *p);
  * info[0] waves per scoring workgroup, [1] 32-row blocks per wave, [2] row super-blocks per KV group,
  * [3] keys per chunk of the scoring sweeps, [4] unmasked chunks over all sequences, [5] keys per LDS
  * tile, [6] parts a row is split into for selection (1: one workgroup per row), [7] keys per such
- * part.  Returns SPECKV_OK or the reason the parameters are rejected. */
-#define SPECKV_PLAN_INFO_WORDS 8
+ * part, [8] kernel of the unmasked scoring sweeps (0: key tiles streamed through LDS, 1: query
+ * rows stationary in LDS), [9] 1 for max reduction.  Returns SPECKV_OK or the reason the
+ * parameters are rejected. */
+#define SPECKV_PLAN_INFO_WORDS 10
 speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_INFO_WORDS]);
 
 /* Importance scores (Eq. 1; Alg. 1 CrossAttention, reduce and pooling steps).
@@ -152,8 +162,10 @@ speckv_status speckv_score_lse(const speckv_params *p, const void *q, const void
  * sequence, KV head) writes the min(c_max, m) candidates with the largest pooled score
  * (equal scores: smaller index first), in ascending order, followed by m..n_in-1.
  * `pooled` must not contain NaN.  Layout: "idx" above.  The workspace is optional: with NULL every
- * row is ranked by one workgroup; with a workspace of speckv_workspace_bytes, calls with few rows
- * of 2^18 keys or more spread each row over several workgroups (same result). */
+ * row is ranked by one workgroup; with a 256-byte-aligned workspace of at least
+ * speckv_select_workspace_bytes (a few MiB; 0 when the call would not use it), calls with few
+ * and very long rows spread each row over several workgroups (same result). */
+size_t speckv_select_workspace_bytes(const speckv_params *p);
 speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t *idx,
                             void *workspace, size_t workspace_bytes, void *stream);
 
@@ -239,12 +251,23 @@ speckv_status speckv_compress_ada(const speckv_params *p, int32_t c_floor, const
  * each widened to [t - n_neighbor, t + n_neighbor] (clipped to the prompt), united with
  * the window m..n_in-1 and emitted ascending without duplicates into idx_out
  * (capacity n_in), with ids_out[r] = token_ids[idx_out[r]] and *count_out (device int32)
- * the number of entries.  p->c_max is ignored. */
+ * the number of entries.  p->c_max, p->reduce_op and p->pool_op are ignored (the reduced form
+ * is a sum with max pooling; invalid values of the two ops are still rejected). */
 size_t specpc_workspace_bytes(const speckv_params *p, int32_t top_k);
 speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
                                    const void *q, const void *k, const int32_t *token_ids,
                                    int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* specpc_select_tokens with per-stage timing marks (see speckv_compress_events): [0] start
+ * [1] after scoring pass 1  [2] after the row-statistics merge  [3] after scoring pass 2
+ * [4] after the cross-layer reduction and pooling  [5] after the top-k selection  [6] after the
+ * neighbour expansion and id gather.  Same results as specpc_select_tokens (Alg. 2, reduced). */
+speckv_status specpc_select_tokens_events(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                          const void *q, const void *k, const int32_t *token_ids,
+                                          int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                          void *workspace, size_t workspace_bytes, void *stream,
+                                          void **events, int32_t n_events);
 
 /* Prompt compression as printed in Sec. 4.2 / Alg. 2.  Needs n_seqs == 1.  q holds the draft
  * model's queries of the n_window last prompt rows followed by the lookahead rows, k its prompt

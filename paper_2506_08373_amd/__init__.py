@@ -12,9 +12,12 @@ from .binding import (  # noqa: F401
     load_library,
     n_keep,
     plan_info,
+    select_workspace_bytes,
     specpc_compress_prompt,
     specpc_compress_workspace_bytes,
     specpc_select_tokens,
+    specpc_select_tokens_events,
+    SPECPC_STAGE_NAMES,
     specpc_workspace_bytes,
     ada_workspace_bytes,
     speckv_compact,

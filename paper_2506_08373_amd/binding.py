@@ -47,7 +47,8 @@ EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv
            "speckv_compress_events", "speckv_score_lse", "speckv_compress_lse",
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
            "specpc_compress_prompt", "speckv_ada_workspace_bytes", "speckv_select_ada",
-           "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info", "speckv_compress_static")
+           "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info", "speckv_compress_static",
+           "specpc_select_tokens_events", "speckv_select_workspace_bytes")
 
 
 def library_path() -> str:
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_total_keep.argtypes = [P]
     lib.speckv_workspace_bytes.restype = ctypes.c_size_t
     lib.speckv_workspace_bytes.argtypes = [P]
+    lib.speckv_select_workspace_bytes.restype = ctypes.c_size_t
+    lib.speckv_select_workspace_bytes.argtypes = [P]
     lib.specpc_workspace_bytes.restype = ctypes.c_size_t
     lib.specpc_workspace_bytes.argtypes = [P, ctypes.c_int32]
     lib.speckv_score.restype = ctypes.c_int
@@ -105,6 +108,10 @@ def load_library() -> ctypes.CDLL:
     lib.specpc_select_tokens.restype = ctypes.c_int
     lib.specpc_select_tokens.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
                                          i32p, vp, ctypes.c_size_t, vp]
+    lib.specpc_select_tokens_events.restype = ctypes.c_int
+    lib.specpc_select_tokens_events.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
+                                                i32p, vp, ctypes.c_size_t, vp,
+                                                ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
     lib.specpc_compress_workspace_bytes.restype = ctypes.c_size_t
     lib.specpc_compress_workspace_bytes.argtypes = [P, ctypes.c_int32]
     lib.specpc_compress_prompt.restype = ctypes.c_int
@@ -195,6 +202,10 @@ def workspace_bytes(p: SpecKVParams) -> int:
     return int(load_library().speckv_workspace_bytes(p.ref()))
 
 
+def select_workspace_bytes(p: SpecKVParams) -> int:
+    return int(load_library().speckv_select_workspace_bytes(p.ref()))
+
+
 def specpc_workspace_bytes(p: SpecKVParams, top_k: int) -> int:
     return int(load_library().specpc_workspace_bytes(p.ref(), top_k))
 
@@ -263,10 +274,10 @@ def speckv_compress_static(p: SpecKVParams, q, k, v, idx, k_out, v_out) -> None:
 
 def plan_info(p: SpecKVParams) -> dict:
     """The host's launch plan for these parameters (diagnostics; needs no GPU)."""
-    out = (ctypes.c_int64 * 8)()
+    out = (ctypes.c_int64 * 10)()
     _check(load_library().speckv_plan_info(p.ref(), out), "speckv_plan_info")
     keys = ("waves", "blocks_per_wave", "row_super_blocks", "chunk_keys", "n_chunks", "tile_keys",
-            "select_parts", "select_part_keys")
+            "select_parts", "select_part_keys", "q_stationary", "reduce_max")
     return dict(zip(keys, (int(x) for x in out)))
 
 
@@ -318,6 +329,19 @@ def specpc_select_tokens(p: SpecKVParams, top_k: int, n_neighbor: int, q, k, tok
         p.ref(), top_k, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
         _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
         _ptr(count_out, torch.int32), wp, wb, _stream()), "specpc_select_tokens")
+
+
+SPECPC_STAGE_NAMES = ("score_pass1", "lse_merge", "score_pass2", "pool", "select", "expand")
+
+
+def specpc_select_tokens_events(p: SpecKVParams, top_k: int, n_neighbor: int, q, k, token_ids, idx_out,
+                                ids_out, count_out, workspace, events) -> None:
+    """`events`: ctypes array of N_STAGE_EVENTS raw hipEvent_t handles (c_void_p)."""
+    wp, wb = _ws(workspace)
+    _check(load_library().specpc_select_tokens_events(
+        p.ref(), top_k, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
+        _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
+        _ptr(count_out, torch.int32), wp, wb, _stream(), events, N_STAGE_EVENTS), "specpc_select_tokens_events", "speckv_select_workspace_bytes")
 
 
 def specpc_compress_workspace_bytes(p: SpecKVParams, l_skip: int) -> int:

@@ -12,13 +12,17 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspeckv.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip"]
+SOURCES = ["api.hip", "score.hip", "score_qs.hip", "select.hip", "compact.hip"]
 
 # Packed fp32 VALU ops are disabled on purpose; the host pass warns that it does not
 # know the feature, which is harmless.
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go to ordinary vector registers (the softmax arithmetic reads them directly);
+    # without this a kernel that may use more than 256 registers gets accumulator-register
+    # results and one copy per score element
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

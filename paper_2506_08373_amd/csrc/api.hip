@@ -100,7 +100,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
     g.HPS = 1; g.PPH = (g.Rp + g.RSB - 1) / g.RSB; g.RS = d.G * g.PPH;
   }
   const int64_t units = (int64_t)d.L * d.Hkv * g.RS;
-  if (units > 65535) return SPECKV_ERR_UNSUPPORTED;
+  if (units > (int64_t)1 << 24) return SPECKV_ERR_UNSUPPORTED;       // grid sizes stay far below 2^31
   // Keys [0, tail0) of a sequence are complete LDS tiles visible to every observation row
   // (key <= m); they are cut into chunks of KC keys.  The rest is one masked tail chunk.
   const int rowb = d.D * d.elt;
@@ -253,6 +253,8 @@ speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_
   info[0] = pl.g.NW; info[1] = pl.g.MB; info[2] = pl.g.RS; info[3] = pl.g.KC; info[4] = pl.g.n_fast_chunks;
   info[5] = rowb <= 128 ? 256 : rowb <= 256 ? 128 : 64;
   info[6] = pl.sel_parts; info[7] = pl.sel_part_len;
+  info[8] = score_uses_qs(pl) ? 1 : 0;
+  info[9] = pl.d.reduce_max;
   return SPECKV_OK;
 }
 
@@ -262,9 +264,19 @@ size_t speckv_workspace_bytes(const speckv_params *p) {
   return pl.total;
 }
 
+size_t speckv_select_workspace_bytes(const speckv_params *p) {
+  Plan pl;
+  if (build_plan(p, &pl, false, 0) != SPECKV_OK || pl.sel_parts <= 1) return 0;
+  return (size_t)align_up((int64_t)(pl.off_sel_state - pl.off_sel_hist), 256) + (pl.total - pl.off_sel_state);
+}
+
 size_t specpc_workspace_bytes(const speckv_params *p, int32_t top_k) {
   Plan pl;
-  if (top_k < 0 || build_plan(p, &pl, true, top_k) != SPECKV_OK) return 0;
+  if (p == nullptr || top_k < 0) return 0;
+  speckv_params eff = *p;                 // as in specpc_select_tokens: always sum / max pooling
+  eff.reduce_op = SPECKV_REDUCE_SUM;
+  eff.pool_op = SPECKV_POOL_MAX;
+  if (build_plan(&eff, &pl, true, top_k) != SPECKV_OK) return 0;
   return pl.total;
 }
 
@@ -306,14 +318,15 @@ speckv_status speckv_select(const speckv_params *p, const float *pooled, int32_t
   if (pooled == nullptr || idx == nullptr) return SPECKV_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(pooled) & 3u) || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SPECKV_ERR_INVALID_ARG;
   // The workspace is optional here: without it every row is ranked by one workgroup (scratch in
-  // LDS); with it, calls with few and very long rows spread each row over several workgroups.
+  // LDS); with one of speckv_select_workspace_bytes, calls with few and very long rows spread each
+  // row over several workgroups.  Layout: the parts' histograms, then the search state.
   uint32_t *hist = nullptr, *state = nullptr;
-  if (workspace != nullptr) {
-    if ((st = check_ws(pl, workspace, workspace_bytes)) != SPECKV_OK) return st;
-    if (pl.sel_parts > 1) {
-      hist = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + pl.off_sel_hist);
-      state = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + pl.off_sel_state);
-    }
+  if (workspace != nullptr && pl.sel_parts > 1) {
+    const size_t hist_bytes = (size_t)align_up((int64_t)(pl.off_sel_state - pl.off_sel_hist), 256);
+    const size_t need = hist_bytes + (pl.total - pl.off_sel_state);
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need) return SPECKV_ERR_WORKSPACE;
+    hist = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace));
+    state = reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + hist_bytes);
   }
   return from_hip(launch_select(pl, pooled, idx, hist, state, static_cast<hipStream_t>(stream)));
 }
@@ -461,13 +474,17 @@ speckv_status speckv_compress_ada(const speckv_params *p, int32_t c_floor, const
   return from_hip(launch_compact_ada(pl, k, v, idx, head_off, k_out, v_out, hs));
 }
 
-speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
-                                   const void *q, const void *k, const int32_t *token_ids,
-                                   int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
-                                   void *workspace, size_t workspace_bytes, void *stream) {
-  if (top_k < 0 || n_neighbor < 0) return SPECKV_ERR_INVALID_ARG;
+static speckv_status select_tokens_impl(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                        const void *q, const void *k, const int32_t *token_ids,
+                                        int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                        void *workspace, size_t workspace_bytes, void *stream, hipEvent_t *ev) {
+  if (p == nullptr || top_k < 0 || n_neighbor < 0) return SPECKV_ERR_INVALID_ARG;
+  // the reduced form is defined with sum aggregation and max pooling whatever the caller's ops say
+  speckv_params eff = *p;
+  eff.reduce_op = SPECKV_REDUCE_SUM;
+  eff.pool_op = SPECKV_POOL_MAX;
   Plan pl;
-  speckv_status st = build_plan(p, &pl, true, top_k);
+  speckv_status st = build_plan(&eff, &pl, true, top_k);
   if (st != SPECKV_OK) return st;
   if (q == nullptr || k == nullptr || token_ids == nullptr || idx_out == nullptr || ids_out == nullptr ||
       count_out == nullptr) return SPECKV_ERR_INVALID_ARG;
@@ -481,12 +498,36 @@ speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_
   float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
   int32_t *sel = reinterpret_cast<int32_t *>(ws + pl.off_sel);
   hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
-                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs);
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev);
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_reduce_pool_all(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_select_row(pooled, m, count, sel, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
-  return from_hip(launch_expand(sel, count, n_in, pl.d.w, n_neighbor, token_ids, idx_out, ids_out,
-                                count_out, hs));
+  if (ev && hipEventRecord(ev[5], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_expand(sel, count, n_in, pl.d.w, n_neighbor, token_ids, idx_out, ids_out, count_out, hs)) != hipSuccess)
+    return SPECKV_ERR_RUNTIME;
+  if (ev && hipEventRecord(ev[6], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  return SPECKV_OK;
+}
+
+speckv_status specpc_select_tokens(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                   const void *q, const void *k, const int32_t *token_ids,
+                                   int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                   void *workspace, size_t workspace_bytes, void *stream) {
+  return select_tokens_impl(p, top_k, n_neighbor, q, k, token_ids, idx_out, ids_out, count_out, workspace,
+                            workspace_bytes, stream, nullptr);
+}
+
+speckv_status specpc_select_tokens_events(const speckv_params *p, int32_t top_k, int32_t n_neighbor,
+                                          const void *q, const void *k, const int32_t *token_ids,
+                                          int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
+                                          void *workspace, size_t workspace_bytes, void *stream,
+                                          void **events, int32_t n_events) {
+  if (events == nullptr || n_events != SPECKV_N_STAGE_EVENTS) return SPECKV_ERR_INVALID_ARG;
+  for (int i = 0; i < n_events; ++i)
+    if (events[i] == nullptr) return SPECKV_ERR_INVALID_ARG;
+  return select_tokens_impl(p, top_k, n_neighbor, q, k, token_ids, idx_out, ids_out, count_out, workspace,
+                            workspace_bytes, stream, reinterpret_cast<hipEvent_t *>(events));
 }
 
 // Parameters of the layers that take part: the first l_skip layers are dropped by moving the base

@@ -28,86 +28,15 @@
 // is element (8*(i/4) + 4*(l/32) + i%4, l%32).  Both operands take their k-slices from the same
 // 16-byte chunks of the head dimension (half l/32 reads chunks [half*NCS, half*NCS+NCS)), so the
 // contraction is over all d channels whatever order the hardware assigns inside a slice.
+#include <map>
+#include <mutex>
 #include <type_traits>
+#include <utility>
 
-#include "speckv_internal.h"
+#include "score_common.h"
 
 namespace speckv {
 namespace {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
-
-constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
-
-
-// x + (x of the lane 32 away), in every lane, without going through LDS (v_permlane32_swap).
-__device__ inline float add_other_half(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-struct ScoreArgs {
-  Dims d;
-  SeqTab t;
-  ScoreGeom g;
-  const char *q;
-  const char *k;
-  float2 *part;     // [unit][chunk][RSB] (max2, sum) per row, unit = (layer, head, row super-block)
-  float *lse;       // [layer][head][seq][RS*RSB]
-  const float *lse_in;   // optional caller-supplied natural-log normalisers [L][S][R][Hq]
-  float *planes;    // [RS][layer][Hkv*T]
-};
-
-__device__ inline float max_other_half(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-// Number types (values of speckv_dtype) and their element size.
-constexpr int kBf16 = SPECKV_BF16, kF32 = SPECKV_F32, kF16 = SPECKV_F16;
-constexpr int elt_bytes(int dt) { return dt == kF32 ? 4 : 2; }
-
-// One 16-byte chunk of the head dimension per lane half: 8 bf16/f16 or 4 f32 products per row pair.
-template <int DT>
-__device__ inline f32x16 mma_chunk(u32x4 a, u32x4 b, f32x16 acc);
-
-template <>
-__device__ inline f32x16 mma_chunk<kBf16>(u32x4 a, u32x4 b, f32x16 acc) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-}
-
-template <>
-__device__ inline f32x16 mma_chunk<kF16>(u32x4 a, u32x4 b, f32x16 acc) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
-}
-
-template <>
-__device__ inline f32x16 mma_chunk<kF32>(u32x4 a, u32x4 b, f32x16 acc) {
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-  return acc;
-}
-
-template <int ELT, int D>
-struct Tile {
-  static constexpr int ROWB = D * ELT;          // bytes per key / query row
-  static constexpr int C16 = ROWB / 16;         // 16-byte chunks per row
-  static constexpr int NCS = C16 / 2;           // chunk steps (each lane half owns NCS chunks)
-  static constexpr int KT = ROWB <= 128 ? 256 : ROWB <= 256 ? 128 : 64;   // keys per LDS tile (32 KiB)
-  static constexpr int TILE_BYTES = KT * ROWB;
-  static constexpr int RPB = ROWB >= 256 ? 1 : 256 / ROWB;   // rows per 256-byte bank sweep
-  static constexpr int SWZ = (C16 < 16 ? C16 : 16) - 1;      // xor mask applied to the chunk index
-  __device__ static inline int swizzle(int row) { return (row / RPB) & SWZ; }
-};
 
 template <int ELT, int D, int MB, int NW>
 constexpr size_t score_lds_bytes() {
@@ -139,8 +68,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   int unit, s, chunk, key_begin, key_end;
   if (MASKED) {
-    unit = blockIdx.y;
-    s = blockIdx.x;
+    unit = blockIdx.x;
+    s = blockIdx.y;
     chunk = A.g.n_fast_chunks + s;
     key_begin = A.t.tail0[s];
     key_end = A.t.cu[s + 1] - A.t.cu[s];
@@ -577,8 +506,7 @@ __global__ __launch_bounds__(256) void lse_import_kernel(ScoreArgs A) {
 
 template <typename K>
 hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, grid, block, lds, st, A);
   return hipGetLastError();
@@ -588,7 +516,9 @@ template <int DT, int D, int MB, int NW, int PASS, int RED>
 hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
   const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
   hipError_t e;
-  if (A.g.n_fast_chunks > 0) {
+  if (A.g.n_fast_chunks > 0 && qs_supported(A)) {
+    if ((e = launch_qs_sweep(A, PASS, st)) != hipSuccess) return e;
+  } else if (A.g.n_fast_chunks > 0) {
     const int64_t items = (int64_t)A.g.n_fast_chunks * A.d.L * A.d.Hkv;
     const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS;
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -597,7 +527,7 @@ hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
     else e = launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     if (e != hipSuccess) return e;
   }
-  return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, true>, A, dim3(A.d.S, units), dim3(NW * 64), lds, st);
+  return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, true>, A, dim3(units, A.d.S), dim3(NW * 64), lds, st);
 }
 
 template <int DT, int D, int MB, int NW>
@@ -635,6 +565,29 @@ hipError_t dispatch_geom(const ScoreArgs &A, hipStream_t st, hipEvent_t *ev) {
 }
 
 }  // namespace
+
+// Raises a kernel's dynamic LDS limit; the runtime call is made once per (device, kernel, size)
+// and remembered, so a fused call does not pay for it on every launch.
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void *>, size_t> granted;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  size_t &have = granted[std::make_pair(dev, kernel)];
+  if (have >= bytes && have != 0) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) have = bytes;
+  return e;
+}
+
+bool score_uses_qs(const Plan &pl) {
+  ScoreArgs A;
+  A.d = pl.d; A.t = pl.t; A.g = pl.g;
+  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr;
+  return qs_supported(A);
+}
 
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
                         float *planes, hipStream_t st, hipEvent_t *events, const float *lse_in) {

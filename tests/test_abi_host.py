@@ -18,6 +18,9 @@ def lib():
     return S.load_library()
 
 
+PLAN_INFO_WORDS = 10     # SPECKV_PLAN_INFO_WORDS of include/speckv.h
+
+
 def base_params(**kw):
     args = dict(n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=64, seq_lens=[300, 500], n_window=16,
                 n_lookahead=16, pool_k=7, c_max=64, sm_scale=0.125, dtype=torch.bfloat16)
@@ -34,6 +37,11 @@ def test_every_declared_symbol_is_exported(lib, repo_root):
     for name in declared:
         assert hasattr(lib, name), "header declares %s but the library does not export it" % name
     assert set(binding.EXPORTS) == declared
+
+
+def test_plan_info_word_count_matches_the_header(repo_root):
+    header = open(os.path.join(repo_root, "include", "speckv.h")).read()
+    assert int(re.search(r"#define SPECKV_PLAN_INFO_WORDS (\d+)", header).group(1)) == PLAN_INFO_WORDS
 
 
 def test_status_strings(lib):
@@ -76,6 +84,19 @@ def test_unsupported_configurations(lib, kw):
     p = base_params(**kw)
     st = lib.speckv_compress(p.ref(), 256, 256, 256, 256, 256, 256, 256, 1 << 40, None)
     assert st == -2
+
+
+def test_select_workspace_is_small_and_checked(lib):
+    """Selection needs scratch only when few, very long rows are split over workgroups; the size is
+    a few MiB, far below the scoring workspace, and a smaller buffer is refused before any launch."""
+    short = base_params()
+    assert S.select_workspace_bytes(short) == 0
+    long_rows = base_params(n_layers=1, seq_lens=[600000], c_max=4096)
+    need = S.select_workspace_bytes(long_rows)
+    assert 0 < need < S.workspace_bytes(long_rows) and need % 256 == 0 and need < (16 << 20)
+    assert S.plan_info(long_rows)["select_parts"] > 1
+    assert lib.speckv_select(long_rows.ref(), 256, 256, 256, need - 1, None) == -3
+    assert lib.speckv_select(long_rows.ref(), 256, 256, 257, need, None) == -3      # misaligned
 
 
 def test_null_misaligned_and_workspace_errors(lib):
@@ -181,7 +202,7 @@ def test_plan_invariants_over_random_shapes(lib):
             continue
         p = S.SpecKVParams(n_layers=L, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=d, seq_lens=lens,
                            n_window=w_, n_lookahead=a_, pool_k=7, c_max=1024, sm_scale=0.1, dtype=dt)
-        out = (ctypes.c_int64 * 8)()
+        out = (ctypes.c_int64 * PLAN_INFO_WORDS)()
         st = lib.speckv_plan_info(p.ref(), out)
         if st == -2:
             continue                                           # outside the supported envelope

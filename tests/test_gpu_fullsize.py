@@ -29,11 +29,11 @@ def S():
     return lib
 
 
-def run_workload(S, w, want_scores=True):
+def run_workload(S, w, want_scores=True, reduce="sum"):
     data = workloads.generate(w, device="cuda")
     q, k, v = data["q"], data["k"], data["v"]
     p = S.SpecKVParams.for_tensors(q, k, seq_lens=w.seq_lens, n_window=w.n_window, pool_k=w.pool_k,
-                                   c_max=w.c_max, sm_scale=w.sm_scale)
+                                   c_max=w.c_max, sm_scale=w.sm_scale, reduce=reduce)
     KT, L, H, d = S.total_keep(p), w.n_layers, w.n_kv_heads, w.head_dim
     idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
     k_out = torch.empty((L, H * KT, d), dtype=w.torch_dtype, device="cuda")
@@ -81,7 +81,7 @@ def check_structure_everywhere(w, data, idx, k_out, v_out):
                 assert torch.equal(vo[layer, g], vsrc[layer, rows[layer, g], g])
 
 
-def check_sampled_heads(w, data, idx, pooled, samples):
+def check_sampled_heads(w, data, idx, pooled, samples, reduce="sum"):
     """Element-by-element comparison with the oracle on sampled (layer, seq, head) triples."""
     keeps, ck = keep_layout(w)
     cu = w.cu_seqlens
@@ -91,9 +91,10 @@ def check_sampled_heads(w, data, idx, pooled, samples):
         n, m = w.seq_lens[s], w.seq_lens[s] - w.n_window
         qh = workloads.to_float64(data["q"][layer, s, :, g * G:(g + 1) * G])
         kh = workloads.to_float64(data["k"][layer, cu[s]:cu[s + 1], g:g + 1])
-        raw = orc.raw_scores(qh, kh, w.n_window, w.sm_scale)
+        raw = orc.raw_scores(qh, kh, w.n_window, w.sm_scale, reduce=reduce)
         ref_pooled = orc.pooled_scores(raw, w.n_window, w.pool_k)[0]
-        assert abs(raw.sum() - w.n_rows * G) < 1e-6 * w.n_rows * G        # oracle sanity at this size
+        if reduce == "sum":
+            assert abs(raw.sum() - w.n_rows * G) < 1e-6 * w.n_rows * G    # oracle sanity at this size
         a = H * cu[s] + g * n
         got = pooled[layer, a:a + m].double().cpu().numpy()
         tol = REL_TOL * np.abs(ref_pooled) + ABS_FLOOR * np.abs(ref_pooled).max()
@@ -236,3 +237,18 @@ def test_one_million_token_prompt(S):
     data, p, idx, k_out, v_out, pooled = run_workload(S, w)
     check_structure_everywhere(w, data, idx, k_out, v_out)
     check_sampled_heads(w, data, idx, pooled, [(0, 0, 1)])
+
+
+def test_paper_evaluated_setting_128k(S):
+    """The hyper-parameter table's SpecKV column at the 128K shape: Reduction = Max (Alg. 1
+    MaxReduce), Pool = Max with k = 7, n_window = 32, 96 lookahead rows, budget C_max - n_window
+    non-window keys.  Structure on every layer and head; every KV head of two layers against the
+    oracle element by element."""
+    import dataclasses
+    base = workloads.llama8b_layer(n_in=131072, c_max=2048 - 32, n_layers=4, seed=7, name="paper_setting_128k")
+    w = dataclasses.replace(base, n_window=32, n_lookahead=96, pool_k=7)
+    data, p, idx, k_out, v_out, pooled = run_workload(S, w, reduce="max")
+    assert S.plan_info(p)["reduce_max"] == 1
+    check_structure_everywhere(w, data, idx, k_out, v_out)
+    check_sampled_heads(w, data, idx, pooled, [(layer, 0, g) for layer in (0, 3) for g in range(w.n_kv_heads)],
+                        reduce="max")
