@@ -61,16 +61,27 @@ def raw_scores(q, k, n_window: int, sm_scale: float, reduce: str = "sum") -> Lis
 
 
 def max_pool(row: Sequence[float], pool_k: int) -> List[float]:
+    """Window j - k//2 .. j + (k-1)//2 (symmetric for odd k; for even k one position more before j
+    than after it), clipped to the row."""
     m = len(row)
-    half = pool_k // 2
-    return [max(row[t] for t in range(max(0, j - half), min(m - 1, j + half) + 1)) for j in range(m)]
+    out = []
+    for j in range(m):
+        best = None
+        for t in range(j - pool_k // 2, j - pool_k // 2 + pool_k):      # the k positions of the window
+            if 0 <= t < m and (best is None or row[t] > best):
+                best = row[t]
+        out.append(best)
+    return out
 
 
 def avg_pool(row: Sequence[float], pool_k: int) -> List[float]:
+    """Mean over the same k positions with zeros outside the row."""
     m = len(row)
-    half = pool_k // 2
-    return [math.fsum(row[t] for t in range(max(0, j - half), min(m - 1, j + half) + 1)) / pool_k
-            for j in range(m)]
+    out = []
+    for j in range(m):
+        out.append(math.fsum(row[t] for t in range(j - pool_k // 2, j - pool_k // 2 + pool_k) if 0 <= t < m)
+                   / pool_k)
+    return out
 
 
 def select_top(pooled: Sequence[float], count: int) -> List[int]:

@@ -30,6 +30,9 @@ Readings taken where the paper is silent or at odds with itself:
   (the group is averaged as in App. C.2, times a constant);
 * by default pooling is MAX pooling (hyper-parameter table), stride 1, same
   length, the neighbourhood clipped at both ends of the candidate range [0, m);
+  an even kernel k (the table's SpecPC column: 64 / 32) covers k // 2 positions
+  before j and k // 2 - 1 after it (the library call with padding k // 2, first m
+  outputs kept);
   with pool="avg" (Alg. 1 AvgPool1D step) it is the mean over the k positions of
   the window with zeros outside [0, m) (the usual library convention: padding
   k//2, padded zeros counted in the divisor);
@@ -145,34 +148,49 @@ def raw_scores(q: np.ndarray, k: np.ndarray, n_window: int, sm_scale: float,
 # --------------------------------------------------------------------------- #
 # Pooling (Alg. 1 pooling step; table: Max, k = 7)
 # --------------------------------------------------------------------------- #
+def pool_window(pool_k: int):
+    """Positions a pooling kernel covers around j: j - before .. j + after.
+
+    Odd k: the symmetric window.  Even k (the hyper-parameter table's SpecPC column uses 64 and
+    32): the window of the usual library call with padding k // 2, whose first m outputs are
+    kept, i.e. k // 2 positions before j and k // 2 - 1 after it.  One formula covers both.
+    """
+    if pool_k < 1:
+        raise ValueError("pool_k must be >= 1")
+    return pool_k // 2, (pool_k - 1) // 2
+
+
 def max_pool_1d(x: np.ndarray, pool_k: int) -> np.ndarray:
-    """Same-length max pooling along the last axis, window clipped at the ends."""
-    if pool_k < 1 or pool_k % 2 == 0:
-        raise ValueError("pool_k must be odd and >= 1")
+    """Same-length max pooling along the last axis, window (see pool_window) clipped at the ends."""
+    before, after = pool_window(pool_k)
     x = np.asarray(x, dtype=np.float64)
     m = x.shape[-1]
-    half = pool_k // 2
     out = x.copy()
-    for t in range(1, half + 1):
+    for t in range(1, before + 1):
         if t >= m:
             break
         out[..., t:] = np.maximum(out[..., t:], x[..., :-t])      # neighbour j - t
+    for t in range(1, after + 1):
+        if t >= m:
+            break
         out[..., :-t] = np.maximum(out[..., :-t], x[..., t:])     # neighbour j + t
     return out
 
 
 def avg_pool_1d(x: np.ndarray, pool_k: int) -> np.ndarray:
-    """Same-length mean over k positions along the last axis, zeros outside the array."""
-    if pool_k < 1 or pool_k % 2 == 0:
-        raise ValueError("pool_k must be odd and >= 1")
+    """Same-length mean over the k positions of pool_window along the last axis, zeros outside the
+    array (the divisor is always k)."""
+    before, after = pool_window(pool_k)
     x = np.asarray(x, dtype=np.float64)
     m = x.shape[-1]
-    half = pool_k // 2
     out = x.copy()
-    for t in range(1, half + 1):
+    for t in range(1, before + 1):
         if t >= m:
             break
         out[..., t:] += x[..., :-t]
+    for t in range(1, after + 1):
+        if t >= m:
+            break
         out[..., :-t] += x[..., t:]
     return out / pool_k
 
@@ -358,7 +376,7 @@ def specpc_compress_prompt(q: np.ndarray, k: np.ndarray, token_ids: np.ndarray, 
     q [L, R, Hq, d] (window rows first, then the lookahead rows), k [L, n, Hkv, d].  The first
     l_skip layers are ignored; window row j is weighted j / n_window; the weighted probabilities
     are max-reduced over layers, heads and rows; AvgPool1D(pool_k) then MaxPool1D(n_neighbor)
-    (both odd here, zero / clipped padding as in avg_pool_1d / max_pool_1d); the top c_max
+    (zero / clipped padding and the window of pool_window for even kernels); the top c_max
     non-window tokens plus the window are kept, ascending.
     """
     n = k.shape[1]

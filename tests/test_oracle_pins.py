@@ -142,13 +142,15 @@ def test_oracle_matches_brute_force_end_to_end():
 
 
 # ------------------------------------------------------------------ pooling
-@pytest.mark.parametrize("pool_k", [1, 3, 7, 9])
-@pytest.mark.parametrize("m", [1, 2, 5, 64])
+@pytest.mark.parametrize("pool_k", [1, 2, 3, 4, 7, 8, 9, 64])
+@pytest.mark.parametrize("m", [1, 2, 5, 64, 100])
 def test_max_pool_matches_library_and_loop(pool_k, m):
+    """Odd and even kernels: the library call with padding k // 2 (an even kernel yields m + 1
+    outputs, of which the first m are the same-length result) and a scalar loop."""
     rng = np.random.default_rng(pool_k * 100 + m)
     x = rng.random((3, m))
     got = orc.max_pool_1d(x, pool_k)
-    lib = F.max_pool1d(torch.from_numpy(x)[None], pool_k, stride=1, padding=pool_k // 2)[0].numpy()
+    lib = F.max_pool1d(torch.from_numpy(x)[None], pool_k, stride=1, padding=pool_k // 2)[0].numpy()[:, :m]
     np.testing.assert_array_equal(got, lib)
     for r in range(3):
         assert got[r].tolist() == bf.max_pool(x[r].tolist(), pool_k)
@@ -416,18 +418,35 @@ def test_row_weights_and_head_max():
         np.testing.assert_allclose(got[g], stack.max(axis=(0, 1)), rtol=1e-14)
 
 
-@pytest.mark.parametrize("pool_k", [1, 3, 7])
-@pytest.mark.parametrize("m", [1, 4, 50])
+@pytest.mark.parametrize("pool_k", [1, 2, 3, 4, 7, 32, 64])
+@pytest.mark.parametrize("m", [1, 4, 50, 130])
 def test_avg_pool_matches_library_and_loop(pool_k, m):
     x = np.random.default_rng(pool_k + m).random((2, m))
     got = orc.avg_pool_1d(x, pool_k)
     lib = F.avg_pool1d(torch.from_numpy(x)[None], pool_k, stride=1, padding=pool_k // 2,
-                       count_include_pad=True)[0].numpy()
+                       count_include_pad=True)[0].numpy()[:, :m]
     np.testing.assert_allclose(got, lib, rtol=1e-13, atol=1e-16)
     for r in range(2):
         np.testing.assert_allclose(got[r], bf.avg_pool(x[r].tolist(), pool_k), rtol=1e-13)
-    np.testing.assert_allclose(got.sum(), sum(x[:, j].sum() * (min(m - 1, j + pool_k // 2) - max(0, j - pool_k // 2) + 1)
-                                              for j in range(m)) / pool_k, rtol=1e-12)
+    # mass identity: x[j] is counted once by every output whose window holds j, i.e. by the
+    # outputs j - (k-1)//2 .. j + k//2 that exist
+    covers = [min(m - 1, j + pool_k // 2) - max(0, j - (pool_k - 1) // 2) + 1 for j in range(m)]
+    np.testing.assert_allclose(got.sum(), sum(x[:, j].sum() * covers[j] for j in range(m)) / pool_k, rtol=1e-12)
+
+
+def test_even_pooling_kernels_on_a_hand_worked_row():
+    """k = 2 looks one position back, k = 4 two back and one ahead (hyper-parameter table, SpecPC
+    column: kernel sizes 64 / 32).  The mirrored convention (more positions ahead than back) gives
+    different numbers, so a flipped window cannot pass."""
+    x = np.array([1.0, 2.0, 3.0, 4.0])
+    assert orc.pool_window(2) == (1, 0) and orc.pool_window(4) == (2, 1) and orc.pool_window(7) == (3, 3)
+    assert orc.max_pool_1d(x, 2).tolist() == [1.0, 2.0, 3.0, 4.0]
+    assert orc.avg_pool_1d(x, 2).tolist() == [0.5, 1.5, 2.5, 3.5]
+    assert orc.max_pool_1d(x, 4).tolist() == [2.0, 3.0, 4.0, 4.0]
+    assert orc.avg_pool_1d(x, 4).tolist() == [0.75, 1.5, 2.5, 2.25]
+    mirrored_max_k2 = [max(x[j:j + 2]) for j in range(4)]              # j .. j + 1
+    assert mirrored_max_k2 != orc.max_pool_1d(x, 2).tolist()
+    assert bf.max_pool(x.tolist(), 4) == [2.0, 3.0, 4.0, 4.0] and bf.avg_pool(x.tolist(), 2) == [0.5, 1.5, 2.5, 3.5]
 
 
 def test_paper_setting_end_to_end_vs_brute_force():
@@ -445,13 +464,14 @@ def test_paper_setting_end_to_end_vs_brute_force():
 
 
 # ------------------------------------------------------------------ prompt compression (Alg. 2)
-def test_specpc_alg2_matches_library_composition():
+@pytest.mark.parametrize("pk,nn", [(5, 9), (6, 8), (64, 32)])
+def test_specpc_alg2_matches_library_composition(pk, nn):
     w = workloads.specpc_draft(n_in=300, n_layers=4, name="c5_alg2")
     w = workloads.SpecKVWorkload(**{**w.__dict__, "n_lookahead": 2})
     t = workloads.generate(w)
     ids = workloads.generate_token_ids(w, vocab=5000)
     q, k = workloads.to_float64(t["q"][:, 0]), workloads.to_float64(t["k"])
-    n, nw, l_skip, pk, nn, cm = 300, w.n_window, 1, 5, 9, 40
+    n, nw, l_skip, cm = 300, w.n_window, 1, 40
     res = orc.specpc_compress_prompt(q, k, ids.numpy(), nw, pk, nn, cm, l_skip, w.sm_scale)
     # library route: stack the weighted probabilities and take one amax over layers, heads, rows
     m = n - nw
@@ -467,8 +487,8 @@ def test_specpc_alg2_matches_library_composition():
                 logits[i, m + i + 1:] = float("-inf")
             best = torch.maximum(best, (torch.softmax(logits, 1) * wts[:, None]).amax(0))
     np.testing.assert_allclose(res["raw"], best.numpy(), rtol=1e-12)
-    s1 = F.avg_pool1d(best[None, None, :m], pk, stride=1, padding=pk // 2)
-    s2 = F.max_pool1d(s1, nn, stride=1, padding=nn // 2)[0, 0]
+    s1 = F.avg_pool1d(best[None, None, :m], pk, stride=1, padding=pk // 2)[..., :m]
+    s2 = F.max_pool1d(s1, nn, stride=1, padding=nn // 2)[0, 0, :m]
     np.testing.assert_allclose(res["pooled"], s2.numpy(), rtol=1e-12)
     order = torch.sort(s2, descending=True, stable=True).indices[:cm]
     assert res["sel"].tolist() == sorted(order.tolist())
