@@ -74,10 +74,13 @@ typedef enum { SPECKV_BF16 = 0, SPECKV_F32 = 1, SPECKV_F16 = 2 } speckv_dtype;
  * Max").  Either way the per-head results of a GQA group are added (App. C.2 averages them). */
 typedef enum { SPECKV_REDUCE_SUM = 0, SPECKV_REDUCE_MAX = 1 } speckv_reduce_op;
 
-/* Local pooling with kernel pool_k (Alg. 1 pooling step).  MAX: neighbourhood clipped to the
- * candidates [0, m) (hyper-parameter table).  AVG: mean over the pool_k positions with zeros
- * outside [0, m), i.e. the divisor is always pool_k (the listing's AvgPool1D with the usual
- * library padding convention). */
+/* Local pooling with kernel pool_k (Alg. 1 pooling step).  The window of key j is
+ * j - pool_k/2 .. j + (pool_k-1)/2 (integer division): symmetric for odd kernels; an even kernel
+ * (hyper-parameter table, SpecPC column: 64 / 32) reaches one position further back than ahead,
+ * which is the usual library call with padding pool_k/2 keeping the first m outputs.
+ * MAX: neighbourhood clipped to the candidates [0, m) (hyper-parameter table).  AVG: mean over the
+ * pool_k positions with zeros outside [0, m), i.e. the divisor is always pool_k (the listing's
+ * AvgPool1D with the usual library padding convention). */
 typedef enum { SPECKV_POOL_MAX = 0, SPECKV_POOL_AVG = 1 } speckv_pool_op;
 
 /* Limits (a request beyond them returns SPECKV_ERR_UNSUPPORTED):
@@ -100,7 +103,7 @@ typedef struct {
   int32_t head_dim;    /* 64 or 128                                                          */
   int32_t n_window;    /* >= 0; every sequence needs n_in >= max(1, n_window)                */
   int32_t n_lookahead; /* >= 0; n_window + n_lookahead >= 1                                  */
-  int32_t pool_k;      /* odd, 1..SPECKV_MAX_POOL_K                                          */
+  int32_t pool_k;      /* 1..SPECKV_MAX_POOL_K; window j - k/2 .. j + (k-1)/2                */
   int32_t c_max;       /* >= 0: non-window keys kept per KV head (clamped to m)              */
   float sm_scale;      /* > 0, multiplies q.k (1/sqrt(d), or 1 if folded into q)             */
   int32_t dtype;       /* speckv_dtype of q, k, v                                            */
@@ -274,7 +277,8 @@ speckv_status specpc_select_tokens_events(const speckv_params *p, int32_t top_k,
  * keys, for every layer.  Layers below l_skip are ignored; window row j (1-based) is weighted
  * j / n_window; the weighted attention probabilities are max-reduced over layers, heads and
  * rows into one score per prompt token; AvgPool1D(p->pool_k) then MaxPool1D(n_neighbor) over
- * the non-window tokens (both kernels odd; zero padding for the mean, clipping for the max);
+ * the non-window tokens (windows as for speckv_pool_op, odd or even kernels up to
+ * SPECKV_MAX_POOL_K; zero padding for the mean, clipping for the max);
  * the c_max best tokens (p->c_max) and the window are emitted ascending into idx_out
  * (capacity min(c_max, m) + n_window) with ids_out[r] = token_ids[idx_out[r]] and *count_out
  * their number.  p->reduce_op / pool_op are ignored. */

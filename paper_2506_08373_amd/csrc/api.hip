@@ -33,7 +33,7 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (p->n_seqs < 1 || p->n_layers < 1 || p->n_kv_heads < 1 || p->n_q_heads < 1) return SPECKV_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return SPECKV_ERR_INVALID_ARG;
   if (p->n_window < 0 || p->n_lookahead < 0 || p->n_window + (int64_t)p->n_lookahead < 1) return SPECKV_ERR_INVALID_ARG;
-  if (p->pool_k < 1 || p->pool_k % 2 == 0 || p->c_max < 0) return SPECKV_ERR_INVALID_ARG;
+  if (p->pool_k < 1 || p->c_max < 0) return SPECKV_ERR_INVALID_ARG;
   if (!(p->sm_scale > 0.f) || !std::isfinite(p->sm_scale)) return SPECKV_ERR_INVALID_ARG;
   if (p->dtype != SPECKV_BF16 && p->dtype != SPECKV_F32 && p->dtype != SPECKV_F16) return SPECKV_ERR_INVALID_ARG;
   if (p->reduce_op != SPECKV_REDUCE_SUM && p->reduce_op != SPECKV_REDUCE_MAX) return SPECKV_ERR_INVALID_ARG;
@@ -562,7 +562,7 @@ speckv_status specpc_compress_prompt(const speckv_params *p, int32_t l_skip, int
   speckv_params eff;
   speckv_status st = alg2_plan(p, l_skip, &pl, &eff);
   if (st != SPECKV_OK) return st;
-  if (n_neighbor < 1 || n_neighbor % 2 == 0) return SPECKV_ERR_INVALID_ARG;
+  if (n_neighbor < 1) return SPECKV_ERR_INVALID_ARG;
   if (n_neighbor > SPECKV_MAX_POOL_K) return SPECKV_ERR_UNSUPPORTED;
   if (q == nullptr || k == nullptr || token_ids == nullptr || idx_out == nullptr || ids_out == nullptr ||
       count_out == nullptr) return SPECKV_ERR_INVALID_ARG;

@@ -37,7 +37,9 @@ struct PlaneMerge {
 __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge pm,
                                         float *__restrict__ raw, float *__restrict__ pooled,
                                         int n_s, int m, int pool_k, int pool_avg, int j0, float *tile) {
-  const int half = pool_k / 2;
+  // window of key j: j - half .. j + after (symmetric for odd kernels; an even kernel looks one
+  // position further back than ahead, the library convention with padding k / 2)
+  const int half = pool_k / 2, after = (pool_k - 1) / 2;
   const int span = kPoolTile + 2 * half;
   for (int x = threadIdx.x; x < span; x += kPoolThreads) {
     const int jj = j0 - half + x;
@@ -63,7 +65,7 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge
     if (raw != nullptr) raw[j] = center;
     float best = 0.f;
     if (j < m) {
-      const int lo = max(0, j - half), hi = min(m - 1, j + half);
+      const int lo = max(0, j - half), hi = min(m - 1, j + after);
       best = tile[lo - j0 + half];
       if (pool_avg) {
         for (int jj = lo + 1; jj <= hi; ++jj) best += tile[jj - j0 + half];
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(kAllTile * kAllSlices) void reduce_pool_all_kernel(
   __shared__ float part[kAllSlices][kAllTile + SPECKV_MAX_POOL_K + 1];
   const int j0 = blockIdx.x * kAllTile;
   if (j0 >= n_in) return;
-  const int half = pool_k / 2, span = kAllTile + 2 * half;
+  const int half = pool_k / 2, after = (pool_k - 1) / 2, span = kAllTile + 2 * half;   // see reduce_pool_tile
   const int slice = threadIdx.x / kAllTile, lane = threadIdx.x % kAllTile;
   const int n_planes = pm.n_outer * pm.n_inner;
   const int per_slice = (n_planes + kAllSlices - 1) / kAllSlices;
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(kAllTile * kAllSlices) void reduce_pool_all_kernel(
     if (raw != nullptr) raw[j] = tile[x + half];
     float best = 0.f;
     if (j < m) {
-      const int lo = max(0, j - half), hi = min(m - 1, j + half);
+      const int lo = max(0, j - half), hi = min(m - 1, j + after);
       best = tile[lo - j0 + half];
       if (pool_avg) {
         for (int jj = lo + 1; jj <= hi; ++jj) best += tile[jj - j0 + half];

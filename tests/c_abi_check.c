@@ -23,7 +23,7 @@ int main(void) {
   p.head_dim = 96;                                   /* unsupported head dimension */
   if (speckv_plan_info(&p, info) != SPECKV_ERR_UNSUPPORTED) return 4;
   if (speckv_workspace_bytes(&p) != 0) return 5;
-  p.head_dim = 128; p.pool_k = 6;                    /* even pooling kernel */
+  p.head_dim = 128; p.pool_k = 0;                    /* no pooling kernel */
   if (speckv_compress(&p, (void *)256, (void *)256, (void *)256, (int32_t *)256, (void *)256, (void *)256,
                       (void *)256, (size_t)1 << 40, NULL) != SPECKV_ERR_INVALID_ARG) return 6;
   printf("%s\n", speckv_status_string(SPECKV_ERR_WORKSPACE));

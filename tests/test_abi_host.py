@@ -59,7 +59,6 @@ def test_keep_counts_follow_the_budget_rule(lib):
 
 @pytest.mark.parametrize("kw", [
     dict(n_q_heads=7),                       # not a multiple of n_kv_heads
-    dict(pool_k=4),                          # even pooling kernel
     dict(pool_k=0),
     dict(c_max=-1),
     dict(sm_scale=0.0),

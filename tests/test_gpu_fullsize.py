@@ -252,3 +252,40 @@ def test_paper_evaluated_setting_128k(S):
     check_structure_everywhere(w, data, idx, k_out, v_out)
     check_sampled_heads(w, data, idx, pooled, [(layer, 0, g) for layer in (0, 3) for g in range(w.n_kv_heads)],
                         reduce="max")
+
+
+def test_specpc_table_setting_full(S):
+    """Alg. 2 with the hyper-parameter table's SpecPC column on the draft-model shape: window 64,
+    one lookahead row, l_skip = 8, average pooling with kernel 64, max pooling over 64 neighbours,
+    2048 kept tokens, 64K prompt tokens, 16 layers."""
+    import dataclasses
+    base = workloads.specpc_draft()
+    w = dataclasses.replace(base, n_lookahead=1, pool_k=64, c_max=2048, name="c5_table_setting")
+    l_skip, n_neighbor = 8, 64
+    data = workloads.generate(w, device="cuda")
+    ids = workloads.generate_token_ids(w, device="cuda")
+    n, m = w.seq_lens[0], w.seq_lens[0] - w.n_window
+    p = S.SpecKVParams.for_tensors(data["q"], data["k"], seq_lens=w.seq_lens, n_window=w.n_window,
+                                   pool_k=w.pool_k, c_max=w.c_max, sm_scale=w.sm_scale)
+    ws = torch.empty(S.specpc_compress_workspace_bytes(p, l_skip), dtype=torch.uint8, device="cuda")
+    cap = w.c_max + w.n_window
+    idx_out = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    ids_out = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    S.specpc_compress_prompt(p, l_skip, n_neighbor, data["q"], data["k"], ids, idx_out, ids_out, count, ws)
+    torch.cuda.synchronize()
+    assert int(count.item()) == cap
+    got = idx_out.cpu().numpy().astype(np.int64)
+    assert (np.diff(got) > 0).all() and got[-w.n_window:].tolist() == list(range(m, n))
+    assert torch.equal(ids_out, ids[idx_out.long()])
+    ref = orc.specpc_compress_prompt(workloads.to_float64(data["q"][:, 0]), workloads.to_float64(data["k"]),
+                                     ids.cpu().numpy(), w.n_window, w.pool_k, n_neighbor, w.c_max, l_skip,
+                                     w.sm_scale)
+    if np.array_equal(got, ref["idx"]):
+        return
+    pooled = ref["pooled"]
+    tau = np.sort(pooled)[m - w.c_max]
+    band = REL_TOL * abs(tau) + ABS_FLOOR * np.abs(pooled).max()
+    sel = got[:w.c_max]
+    assert np.isin(np.nonzero(pooled > tau + band)[0], sel).all()
+    assert not np.isin(np.nonzero(pooled < tau - band)[0], sel).any()

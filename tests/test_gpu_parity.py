@@ -252,6 +252,13 @@ def test_max_reduction_and_average_pooling_llama_shape(S, reduce, pool):
     check_full_path(S, w, reduce=reduce, pool=pool)
 
 
+@pytest.mark.parametrize("pool_k,pool", [(2, "max"), (8, "avg"), (64, "max")])
+def test_even_pooling_kernels(S, pool_k, pool):
+    """Even kernels look one position further back than ahead (window j - k/2 .. j + k/2 - 1)."""
+    w = workloads.llama8b_layer(n_in=3000 + 41, c_max=300, name="even_pool")
+    check_full_path(S, w, pool_k=pool_k, pool=pool)
+
+
 def test_max_reduction_ragged_gqa7_and_tiny(S):
     w = workloads.ragged_batch(n_layers=2, lo=150, hi=1500, n_seqs=3, seed=9, name="c4_max")
     check_full_path(S, w, c_max=100, reduce="max", pool="avg")
@@ -413,6 +420,9 @@ def test_specpc_select_tokens(S, n_in, top_k, nb):
     (3000, 4, 1, 1, 7, 9, 300),
     (900, 3, 0, 3, 63, 31, 5000),       # budget above m, wide pools
     (1500, 10, 8, 1, 1, 1, 100),        # the paper's l_skip; pools of one
+    (2500, 10, 8, 1, 64, 64, 400),      # the hyper-parameter table's SpecPC column: even kernels of 64
+    (1200, 3, 1, 1, 32, 32, 150),       # ... and of 32 (the smaller draft)
+    (700, 2, 0, 2, 2, 4, 90),           # the smallest even kernels
 ])
 def test_specpc_compress_prompt_alg2(S, n_in, n_layers, l_skip, n_lookahead, pool_k, n_neighbor, c_max):
     base = workloads.specpc_draft(n_in=n_in, n_layers=n_layers, name="c5_alg2")
