@@ -114,6 +114,20 @@ typedef struct {
   int64_t kv_stride_layer, kv_stride_token, kv_stride_head;
   int32_t reduce_op;   /* speckv_reduce_op; 0 (SUM) is the default                           */
   int32_t pool_op;     /* speckv_pool_op; 0 (MAX) is the default                             */
+  const int32_t *n_in_dev; /* DEVICE, optional (NULL: unused).  One int32 holding the number of
+                          prompt tokens that really exist, read by the kernels when they run; it
+                          lets a call follow another that produced the count on the device (the
+                          cascade of Sec. 4.3: prompt compression, then cache compression) without
+                          a host round trip and inside one HIP graph.  Needs n_seqs == 1.  The
+                          host length (n_in / cu_seqlens) is then an UPPER BOUND that sizes grids,
+                          workspace, row strides and output shapes; values outside
+                          [max(1, n_window), host length] are clamped.  With a live length n',
+                          m' = n' - n_window: scores at j >= n' are written as 0, idx holds
+                          min(c_max, m') candidates, the window m'..n'-1 and then -1 up to the
+                          host-sized row; compaction writes zero rows for the -1 entries.
+                          Supported by speckv_score(_lse), speckv_select, speckv_compact and
+                          speckv_compress(_lse, _events, _static); other entry points return
+                          SPECKV_ERR_UNSUPPORTED. */
 } speckv_params;
 
 /* Human-readable name of a status code (static storage). */

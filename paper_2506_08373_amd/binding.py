@@ -39,6 +39,7 @@ class _CParams(ctypes.Structure):
         ("kv_stride_layer", ctypes.c_int64), ("kv_stride_token", ctypes.c_int64),
         ("kv_stride_head", ctypes.c_int64),
         ("reduce_op", ctypes.c_int32), ("pool_op", ctypes.c_int32),
+        ("n_in_dev", ctypes.c_void_p),
     ]
 
 
@@ -128,7 +129,8 @@ class SpecKVParams:
                  seq_lens: Sequence[int], n_window: int, n_lookahead: int, pool_k: int, c_max: int,
                  sm_scale: float, dtype: torch.dtype, reduce: str = "sum", pool: str = "max",
                  q_strides: Optional[Tuple[int, int, int, int]] = None,
-                 kv_strides: Optional[Tuple[int, int, int]] = None):
+                 kv_strides: Optional[Tuple[int, int, int]] = None,
+                 n_in_dev: Optional[torch.Tensor] = None):
         self.seq_lens = [int(x) for x in seq_lens]
         S, R, T = len(self.seq_lens), n_window + n_lookahead, sum(self.seq_lens)
         if q_strides is None:        # contiguous [L, S, R, Hq, d]
@@ -149,7 +151,12 @@ class SpecKVParams:
             q_stride_layer=q_strides[0], q_stride_seq=q_strides[1], q_stride_row=q_strides[2],
             q_stride_head=q_strides[3], kv_stride_layer=kv_strides[0], kv_stride_token=kv_strides[1],
             kv_stride_head=kv_strides[2], reduce_op={"sum": 0, "max": 1}[reduce],
-            pool_op={"max": 0, "avg": 1}[pool])
+            pool_op={"max": 0, "avg": 1}[pool], n_in_dev=None)
+        self.n_in_dev = n_in_dev            # keeps the tensor alive for as long as the parameters
+        if n_in_dev is not None:
+            if not n_in_dev.is_cuda or n_in_dev.dtype != torch.int32 or n_in_dev.numel() < 1:
+                raise ValueError("n_in_dev must be a device int32 tensor")
+            self.c.n_in_dev = n_in_dev.data_ptr()
         self.torch_dtype = dtype
         self.n_layers, self.n_kv_heads, self.head_dim = n_layers, n_kv_heads, head_dim
         self.n_window, self.total_tokens = n_window, T
@@ -159,7 +166,8 @@ class SpecKVParams:
 
     @classmethod
     def for_tensors(cls, q: torch.Tensor, k: torch.Tensor, *, seq_lens, n_window, pool_k, c_max,
-                    sm_scale, reduce: str = "sum", pool: str = "max") -> "SpecKVParams":
+                    sm_scale, reduce: str = "sum", pool: str = "max",
+                    n_in_dev: Optional[torch.Tensor] = None) -> "SpecKVParams":
         """q [L, S, R, Hq, d], k [L, T, Hkv, d] (any strides with d contiguous)."""
         if q.dim() != 5 or k.dim() != 4 or q.stride(-1) != 1 or k.stride(-1) != 1:
             raise ValueError("expected q [L,S,R,Hq,d] and k [L,T,Hkv,d] with contiguous d")
@@ -168,7 +176,7 @@ class SpecKVParams:
                    n_window=n_window, n_lookahead=R - n_window, pool_k=pool_k, c_max=c_max,
                    sm_scale=sm_scale, dtype=q.dtype, reduce=reduce, pool=pool,
                    q_strides=tuple(q.stride()[:4]),
-                   kv_strides=tuple(k.stride()[:3]))
+                   kv_strides=tuple(k.stride()[:3]), n_in_dev=n_in_dev)
 
 
 def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:

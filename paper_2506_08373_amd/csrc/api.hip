@@ -82,6 +82,12 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   }
   d.T = t.cu[d.S];
   d.KT = t.ck[d.S];
+  // a device-side token count replaces the host's length inside the kernels (one sequence only)
+  d.n_dev = p->n_in_dev;
+  if (d.n_dev != nullptr) {
+    if (d.S != 1 || one_row_per_call) return SPECKV_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(d.n_dev) & 3u) return SPECKV_ERR_INVALID_ARG;
+  }
 
   // scoring geometry.  Every head's R rows are padded to Rp (a multiple of the 32-row MFMA block)
   // so that no block mixes heads; (waves, blocks per wave): small groups use 4 waves, larger ones
@@ -416,6 +422,7 @@ static speckv_status ada_plan(const speckv_params *p, int32_t c_floor, Plan *pl)
   speckv_status st = build_plan(p, pl, false, 0);
   if (st != SPECKV_OK) return st;
   if (c_floor < 0) return SPECKV_ERR_INVALID_ARG;
+  if (pl->d.n_dev != nullptr) return SPECKV_ERR_UNSUPPORTED;    // shared budgets take host-side lengths only
   if (pl->d.Hkv > SPECKV_MAX_ADA_HEADS) return SPECKV_ERR_UNSUPPORTED;
   return SPECKV_OK;
 }

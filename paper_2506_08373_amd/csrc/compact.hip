@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(
   const int s = (unit / d.Hkv) % d.S;
   const int layer = unit / (d.Hkv * d.S);
   const int n_keep = t.ck[s + 1] - t.ck[s];
-  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int n_s = live_len(d, t, s);
   const int rows_per_step = kThreads >> lpr_shift;
   const int r0 = blk * rows_per_step * kUnroll;
   if (r0 >= n_keep) return;

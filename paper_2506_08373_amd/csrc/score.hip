@@ -71,8 +71,6 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     unit = blockIdx.x;
     s = blockIdx.y;
     chunk = A.g.n_fast_chunks + s;
-    key_begin = A.t.tail0[s];
-    key_end = A.t.cu[s + 1] - A.t.cu[s];
   } else {
     // 1-D grid.  Workgroups go to the 8 XCDs round-robin by their linear id and each XCD has its
     // own L2, so the RS row super-blocks that sweep the SAME keys of a (layer, head) get ids 8
@@ -85,13 +83,20 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
     unit = (item / A.g.n_fast_chunks) * A.g.RS + (within >> 3);
     s = 0;
     while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
+  }
+  const int n_host = A.t.cu[s + 1] - A.t.cu[s];          // row stride of the score layouts
+  const int n_s = live_len(d, A.t, s);                    // tokens that exist (device-side count honoured)
+  const int tail0 = live_tail0(d, A.t, s, n_s, KT);
+  if (MASKED) {
+    key_begin = tail0;
+    key_end = n_s;
+  } else {
     key_begin = (chunk - A.t.cc[s]) * A.g.KC;
-    key_end = min(A.t.tail0[s], key_begin + A.g.KC);
+    key_end = min(tail0, key_begin + A.g.KC);             // a chunk past a shorter live prompt is empty
   }
   const int rs = unit % A.g.RS;
   const int g = (unit / A.g.RS) % d.Hkv;
   const int layer = unit / (A.g.RS * d.Hkv);
-  const int n_s = A.t.cu[s + 1] - A.t.cu[s];
   const int m = n_s - d.w;
   const int ntiles = (key_end - key_begin + KT - 1) / KT;
   const float c2 = d.sm_scale * 1.4426950408889634f;
@@ -220,7 +225,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   // cross-wave merge of the column partials of one finished tile (pass 2)
   float *plane_out = nullptr;
   if (PASS == 2)
-    plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s;
+    plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_host;
   const int blocks_per_head = (A.g.PPH == 1 ? A.g.Rp : RSB) / 32;
   const bool head_max = d.head_max != 0;
 #define SPECKV_FLUSH_TILE(tile_)                                                             \

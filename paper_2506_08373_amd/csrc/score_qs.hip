@@ -111,12 +111,13 @@ __global__ __launch_bounds__(kQsWaves * 64) void score_qs_kernel(ScoreArgs A) {
   const int unit = (item / A.g.n_fast_chunks) * A.g.RS + (within >> 3);
   int s = 0;
   while (s + 1 < d.S && A.t.cc[s + 1] <= chunk) ++s;
+  const int n_host = A.t.cu[s + 1] - A.t.cu[s];          // row stride of the score layouts
+  const int n_live = live_len(d, A.t, s);                 // tokens that exist (device-side count honoured)
   const int key_begin = (chunk - A.t.cc[s]) * A.g.KC;
-  const int key_end = min(A.t.tail0[s], key_begin + A.g.KC);
+  const int key_end = min(live_tail0(d, A.t, s, n_live, TL::KT), key_begin + A.g.KC);
   const int rs = unit % A.g.RS;
   const int g = (unit / A.g.RS) % d.Hkv;
   const int layer = unit / (A.g.RS * d.Hkv);
-  const int n_s = A.t.cu[s + 1] - A.t.cu[s];
   const int RSB = A.g.RSB;
   const float c2 = d.sm_scale * 1.4426950408889634f;
 
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(kQsWaves * 64) void score_qs_kernel(ScoreArgs A) {
   __syncthreads();
 
   // ---- this wave's keys: steps wv, wv + NW, ... of STEP keys each
-  const int nsteps = (key_end - key_begin) / STEP;          // chunks are whole LDS tiles of >= 128 keys
+  const int nsteps = max(0, key_end - key_begin) / STEP;    // chunks are whole LDS tiles of >= 128 keys
   const char *kbase = A.k + ((int64_t)layer * d.kv_sl + (int64_t)A.t.cu[s] * d.kv_st + (int64_t)g * d.kv_sh) * 2;
   const int64_t tokb = d.kv_st * 2;
   uint32_t kofs[KB];                                        // the lane's byte offset inside a step
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kQsWaves * 64) void score_qs_kernel(ScoreArgs A) {
 
   float *plane_out = nullptr;
   if (PASS == 2)
-    plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_s;
+    plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_host;
   const int blocks_per_head = (A.g.PPH == 1 ? A.g.Rp : RSB) / 32;
   const bool head_max = d.head_max != 0;
 

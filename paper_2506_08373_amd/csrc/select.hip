@@ -36,7 +36,8 @@ struct PlaneMerge {
 // Merges the planes per key, writes raw (optional) and pooled for one row tile.
 __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge pm,
                                         float *__restrict__ raw, float *__restrict__ pooled,
-                                        int n_s, int m, int pool_k, int pool_avg, int j0, float *tile) {
+                                        int n_s, int n_row, int m, int pool_k, int pool_avg, int j0,
+                                        float *tile) {
   // window of key j: j - half .. j + after (symmetric for odd kernels; an even kernel looks one
   // position further back than ahead, the library convention with padding k / 2)
   const int half = pool_k / 2, after = (pool_k - 1) / 2;
@@ -60,7 +61,7 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge
   __syncthreads();
   for (int x = threadIdx.x; x < kPoolTile; x += kPoolThreads) {
     const int j = j0 + x;
-    if (j >= n_s) break;
+    if (j >= n_row) break;                                  // entries past the live length read as zero
     const float center = tile[x + half];
     if (raw != nullptr) raw[j] = center;
     float best = 0.f;
@@ -87,10 +88,11 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
   const int g = unit % d.Hkv;
   const int s = (unit / d.Hkv) % d.S;
   const int layer = unit / (d.Hkv * d.S);
-  const int n_s = t.cu[s + 1] - t.cu[s];
-  if (j0 >= n_s) return;
-  const int64_t base = (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
-  reduce_pool_tile(planes + base, pm, raw ? raw + base : nullptr, pooled + base, n_s, n_s - d.w,
+  const int n_row = t.cu[s + 1] - t.cu[s];
+  if (j0 >= n_row) return;
+  const int n_s = live_len(d, t, s);
+  const int64_t base = (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_row;
+  reduce_pool_tile(planes + base, pm, raw ? raw + base : nullptr, pooled + base, n_s, n_row, n_s - d.w,
                    d.pool_k, d.pool_avg, j0, tile);
 }
 
@@ -388,13 +390,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims d, SeqTab t,
   const int g = unit % d.Hkv;
   const int s = (unit / d.Hkv) % d.S;
   const int layer = unit / (d.Hkv * d.S);
-  const int n_s = t.cu[s + 1] - t.cu[s];
-  const int m = n_s - d.w;
+  const int n_row = t.cu[s + 1] - t.cu[s];
+  const int m = live_len(d, t, s) - d.w;
   const int n_keep = t.ck[s + 1] - t.ck[s];
-  const int count = n_keep - d.w;
-  const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  const int count = min(n_keep - d.w, m);                 // a live prompt shorter than the host's bound keeps fewer
+  const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_row;
   int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + (int64_t)g * n_keep;
   for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;   // window, last
+  for (int x = count + d.w + threadIdx.x; x < n_keep; x += kSelThreads) out[x] = -1;   // unused slots
   if (count > 0) select_top_row(row, m, count, out, sh);
 }
 
@@ -415,19 +418,20 @@ __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__
 // it; after the last digit it also knows the keys equal to the threshold per part, so that
 // msel_emit_kernel can place every part's output without another counting pass.
 // State per row: [0] prefix, [1] remaining, [2 .. 2+P) keys above per part, [2+P .. 2+2P) equal.
-struct RowRef { const float *x; int32_t *out; int m, count; };
+struct RowRef { const float *x; int32_t *out; int m, count, n_keep; };
 __device__ __forceinline__ RowRef row_of(const Dims &d, const SeqTab &t, int row, const float *pooled,
                                          int32_t *idx) {
   const int g = row % d.Hkv;
   const int s = (row / d.Hkv) % d.S;
   const int layer = row / (d.Hkv * d.S);
-  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int n_row = t.cu[s + 1] - t.cu[s];
   const int n_keep = t.ck[s + 1] - t.ck[s];
   RowRef r;
-  r.x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
+  r.x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_row;
   r.out = idx ? idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + (int64_t)g * n_keep : nullptr;
-  r.m = n_s - d.w;
-  r.count = n_keep - d.w;
+  r.m = live_len(d, t, s) - d.w;
+  r.count = min(n_keep - d.w, r.m);
+  r.n_keep = n_keep;
   return r;
 }
 
@@ -515,8 +519,10 @@ __global__ __launch_bounds__(kSelThreads) void msel_emit_kernel(Dims d, SeqTab t
   __shared__ SelShared sh;
   const int row = blockIdx.x / P, part = blockIdx.x % P;
   const RowRef r = row_of(d, t, row, pooled, idx);
-  if (part == 0)
+  if (part == 0) {
     for (int x = threadIdx.x; x < d.w; x += kSelThreads) r.out[r.count + x] = r.m + x;   // window, last
+    for (int x = r.count + d.w + threadIdx.x; x < r.n_keep; x += kSelThreads) r.out[x] = -1;   // unused slots
+  }
   const int start = part * part_len;
   const int len = min(part_len, r.m - start);
   if (r.count <= 0 || len <= 0) return;

@@ -33,6 +33,7 @@ struct Dims {
   int64_t q_sl, q_ss, q_sr, q_sh;          // element strides
   int64_t kv_sl, kv_st, kv_sh;
   int64_t T, KT;                           // total tokens, total kept rows
+  const int32_t *n_dev;                    // device-side token count of a one-sequence call, or null
 };
 
 // Geometry of the scoring launches (Alg. 1 CrossAttention + reduce).
@@ -62,6 +63,24 @@ struct Plan {
 };
 
 inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Tokens of sequence s as the kernels see them.  Normally the host's length; with a device-side
+// count (one-sequence calls only) that count, clamped to [max(1, n_window), host length].  The
+// host length stays the row stride of every layout and the bound of every grid.
+__device__ inline int live_len(const Dims &d, const SeqTab &t, int s) {
+  const int n_host = t.cu[s + 1] - t.cu[s];
+  if (d.n_dev == nullptr) return n_host;
+  const int lo = d.w > 1 ? d.w : 1;
+  const int v = *d.n_dev;
+  return v < lo ? lo : (v > n_host ? n_host : v);
+}
+// First key of the masked tail for a live length n: keys below it are whole LDS tiles (kt keys)
+// that every observation row may see (key <= n - n_window).
+__device__ inline int live_tail0(const Dims &d, const SeqTab &t, int s, int n, int kt) {
+  if (d.n_dev == nullptr) return t.tail0[s];
+  const int visible = n - d.w + 1 < n ? n - d.w + 1 : n;
+  return visible / kt * kt;
+}
 
 // Kernel launchers (each returns the hipError of its launches).
 hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const int32_t *idx,

@@ -98,6 +98,24 @@ def test_select_workspace_is_small_and_checked(lib):
     assert lib.speckv_select(long_rows.ref(), 256, 256, 257, need, None) == -3      # misaligned
 
 
+def test_device_side_count_needs_one_sequence_and_supported_entry_points(lib):
+    """n_in_dev is validated on the host like everything else (the pointer itself is never read
+    there): one sequence only, 4-byte aligned, and not for the entry points that do not honour it."""
+    p = base_params(seq_lens=[500])
+    p.c.n_in_dev = 1024
+    need = S.workspace_bytes(p)
+    assert need > 0
+    two = base_params()
+    two.c.n_in_dev = 1024
+    assert S.workspace_bytes(two) == 0
+    assert lib.speckv_compress(two.ref(), 256, 256, 256, 256, 256, 256, 256, 1 << 40, None) == -2
+    p.c.n_in_dev = 1026
+    assert lib.speckv_compress(p.ref(), 256, 256, 256, 256, 256, 256, 256, 1 << 40, None) == -1
+    p.c.n_in_dev = 1024
+    assert lib.speckv_select_ada(p.ref(), 0, 256, 256, 256, 256, 1 << 40, None) == -2
+    assert lib.specpc_select_tokens(p.ref(), 10, 1, 256, 256, 256, 256, 256, 256, 256, 1 << 40, None) == -2
+
+
 def test_null_misaligned_and_workspace_errors(lib):
     p = base_params()
     need = S.workspace_bytes(p)

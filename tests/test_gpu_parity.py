@@ -784,6 +784,138 @@ def test_cascade_prompt_compression_then_cache_compression(S):
             assert np.array_equal(vo[layer, g], v64[layer][orig, g, :])
 
 
+@pytest.mark.parametrize("n_live", [7000, 4097, 3968, 1100, 300, 64])
+def test_device_side_token_count_equals_a_host_length_call(S, n_live):
+    """`n_in_dev`: the kernels read the number of live prompt tokens from device memory; the host
+    length is only an upper bound.  Scores, indices and the compacted cache must equal those of a
+    call whose host length is the live length (on the same first n_live tokens), with zeros / -1 in
+    the slots a shorter prompt leaves unused."""
+    n_cap = 7000
+    w = workloads.llama8b_layer(n_in=n_cap, c_max=512, n_layers=2, name="devlen")
+    t = workloads.generate(w)
+    q, k, v = (t[x].cuda() for x in ("q", "k", "v"))
+    # the window rows of the live prompt are its last n_window tokens: only the key/value prefix matters
+    n_dev = torch.tensor([n_live], dtype=torch.int32, device="cuda")
+    p_dev = S.SpecKVParams.for_tensors(q, k, seq_lens=(n_cap,), n_window=w.n_window, pool_k=w.pool_k,
+                                       c_max=w.c_max, sm_scale=w.sm_scale, n_in_dev=n_dev)
+    k_live, v_live = k[:, :n_live].contiguous(), v[:, :n_live].contiguous()
+    p_host = S.SpecKVParams.for_tensors(q, k_live, seq_lens=(n_live,), n_window=w.n_window, pool_k=w.pool_k,
+                                        c_max=w.c_max, sm_scale=w.sm_scale)
+    L, H, d = w.n_layers, w.n_kv_heads, w.head_dim
+    outs = {}
+    for name, p, kk, vv, n in (("dev", p_dev, k, v, n_cap), ("host", p_host, k_live, v_live, n_live)):
+        KT = S.total_keep(p)
+        pooled = torch.full((L, H * n), -1.0, dtype=torch.float32, device="cuda")
+        raw = torch.full((L, H * n), -1.0, dtype=torch.float32, device="cuda")
+        idx = torch.full((L, H * KT), -7, dtype=torch.int32, device="cuda")
+        k_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
+        v_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
+        ws = alloc_ws(S, p)
+        S.speckv_score(p, q, kk, pooled, raw, ws)
+        S.speckv_compress(p, q, kk, vv, idx, k_out, v_out, ws)
+        torch.cuda.synchronize()
+        outs[name] = (pooled.view(L, H, n), raw.view(L, H, n), idx.view(L, H, KT), k_out.view(L, H, KT, d),
+                      v_out.view(L, H, KT, d))
+    pd, rd, idd, kd, vd = outs["dev"]
+    ph, rh, idh, kh, vh = outs["host"]
+    assert torch.equal(pd[..., :n_live], ph) and torch.equal(rd[..., :n_live], rh)
+    assert bool((pd[..., n_live:] == 0).all()) and bool((rd[..., n_live:] == 0).all())
+    keep_live = idh.shape[-1]
+    assert torch.equal(idd[..., :keep_live], idh)
+    assert bool((idd[..., keep_live:] == -1).all())
+    assert torch.equal(kd[..., :keep_live, :], kh) and torch.equal(vd[..., :keep_live, :], vh)
+    assert bool((kd[..., keep_live:, :] == 0).all()) and bool((vd[..., keep_live:, :] == 0).all())
+
+
+def test_cascade_on_the_device_in_one_graph(S):
+    """SpecKV-PC (Sec. "SpecKV-PC: Cascaded Compression") without a host round trip: the prompt-token
+    selection leaves its data-dependent count on the device, the gather that stands in for the
+    target prefill and the cache compression follow on the same stream, the latter reading the count
+    through `n_in_dev`.  The three steps are captured into one HIP graph; every replay (also after
+    the draft inputs, and with them the count, changed) equals the eager run, and the eager run
+    equals the oracle's composition."""
+    n_in, top_k, nb = 6000, 300, 5
+    wd = workloads.specpc_draft(n_in=n_in, n_layers=3, name="pc_draft_dev")
+    wt = workloads.llama8b_layer(n_in=n_in, c_max=200, n_layers=2, seed=23, name="pc_target_dev")
+    tt = workloads.generate(wt)
+    qt, kt, vt = (tt[x].cuda() for x in ("q", "k", "v"))
+    td = workloads.generate(wd)
+    qd, kd = td["q"].cuda(), td["k"].cuda()
+    ids = workloads.generate_token_ids(wd).cuda()
+    L, H, d = wt.n_layers, wt.n_kv_heads, wt.head_dim
+
+    p1 = make_params(S, wd)
+    ws1 = torch.empty(S.specpc_workspace_bytes(p1, top_k), dtype=torch.uint8, device="cuda")
+    idx_out = torch.empty(n_in, dtype=torch.int32, device="cuda")
+    ids_out = torch.empty(n_in, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    k2, v2 = torch.empty_like(kt), torch.empty_like(vt)             # capacity: the whole prompt
+    p2 = S.SpecKVParams.for_tensors(qt, k2, seq_lens=(n_in,), n_window=wt.n_window, pool_k=wt.pool_k,
+                                    c_max=wt.c_max, sm_scale=wt.sm_scale, n_in_dev=count)
+    KT = S.total_keep(p2)
+    idx = torch.empty((L, H * KT), dtype=torch.int32, device="cuda")
+    k_out = torch.empty((L, H * KT, d), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
+    ws2 = alloc_ws(S, p2)
+
+    def cascade():
+        idx_out.fill_(-1)
+        S.specpc_select_tokens(p1, top_k, nb, qd, kd, ids, idx_out, ids_out, count, ws1)
+        kept = idx_out.clamp(min=0).long()                            # slots past the count are never read
+        torch.index_select(kt, 1, kept, out=k2)
+        torch.index_select(vt, 1, kept, out=v2)
+        S.speckv_compress(p2, qt, k2, v2, idx, k_out, v_out, ws2)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                     # warm-up outside the capture
+        cascade()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cascade()
+
+    counts = []
+    for trial in range(3):
+        if trial:                                                     # other draft inputs: another count
+            t2 = workloads.generate(workloads.specpc_draft(n_in=n_in, n_layers=3, seed=80 + trial, name="pc_draft_dev"))
+            qd.copy_(t2["q"].cuda()); kd.copy_(t2["k"].cuda())
+        for x in (idx, k_out, v_out):
+            x.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (idx.clone(), k_out.clone(), v_out.clone(), idx_out.clone(), count.clone())
+        for x in (idx, k_out, v_out):
+            x.fill_(-5)
+        cascade()
+        torch.cuda.synchronize()
+        assert torch.equal(got[4], count) and torch.equal(got[3], idx_out)
+        assert torch.equal(got[0], idx) and torch.equal(got[1], k_out) and torch.equal(got[2], v_out)
+        counts.append(int(count.item()))
+        if trial == 0:
+            # the eager run against the oracle: stage 1, gather, stage 2
+            ref1 = orc.specpc_select_tokens(workloads.to_float64(td["q"][:, 0]), workloads.to_float64(td["k"]),
+                                            ids.cpu().numpy(), wd.n_window, wd.pool_k, top_k, nb, wd.sm_scale)
+            kept = ref1["idx"]
+            n2 = counts[0]
+            assert n2 == len(kept) and np.array_equal(idx_out[:n2].cpu().numpy(), kept), \
+                "stage 1 differs inside its tolerance band: pick another seed"
+            assert n2 < n_in and n2 - wt.n_window > wt.c_max
+            q64, k64, v64 = (workloads.to_float64(tt[x]) for x in ("q", "k", "v"))
+            idx_h = idx.cpu().numpy().reshape(L, H, KT)
+            ko = k_out.cpu().float().numpy().reshape(L, H, KT, d)
+            for layer in range(L):
+                ref2 = orc.speckv_layer(q64[layer, 0], k64[layer][kept], v64[layer][kept], wt.n_window, wt.pool_k,
+                                        wt.c_max, wt.sm_scale)
+                for g in range(H):
+                    assert_indices_valid(idx_h[layer, g], ref2["pooled"][g], n2, wt.n_window, wt.c_max,
+                                         "device cascade l%d g%d" % (layer, g))
+                    assert np.array_equal(ko[layer, g], k64[layer][kept[idx_h[layer, g]], g, :])
+    assert len(set(counts)) > 1, "the count never changed between replays: nothing was tested"
+
+
 def test_select_signed_zeros_denormals_and_negative_rows(S):
     """-0 and +0 tie (smaller index first), denormal scores keep their order, rows that are all
     negative or mixed select from the right end of the order."""
