@@ -124,6 +124,44 @@ def _blas_threads() -> int:
         return 1
 
 
+def _ceilings(S) -> dict:
+    """Register-resident loops with the sweeps' instruction mix, timed with torch events on the
+    current stream (the probe launches there), and one library GEMM for scale."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    operands = {"random": torch.randn(1 << 16, generator=gen, device="cuda").to(torch.bfloat16),
+                "zeros": torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda")}
+    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    names = {0: "mfma_only", 1: "mfma_softmax", 2: "mfma_softmax_lds512"}
+    iters = 40000
+    res = {}
+    for data, ops in operands.items():
+        for kind, name in names.items():
+            S.probe_ceiling(kind, 2000, ops, out)                    # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = S.probe_ceiling(kind, iters, ops, out)
+            e1.record()
+            torch.cuda.synchronize()
+            res["%s_%s_TFLOPs" % (name, data)] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    a = torch.randn(8192, 8192, generator=gen, device="cuda").to(torch.bfloat16)
+    b = torch.randn(8192, 8192, generator=gen, device="cuda").to(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, b)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        torch.matmul(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    res["library_gemm_8192_bf16_random_TFLOPs"] = round(20 * 2.0 * 8192 ** 3 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return {"ceilings": res, "peak_bf16_TFLOPs": PEAK_MFMA_TFLOPS["bf16"],
+            "note": "256 workgroups x 512 threads, 8 MFMA 32x32x16 bf16 per tile; softmax = 16 x (fma, exp2, add) "
+                    "per lane and tile; lds512 = B operands re-read from LDS every second tile"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,6 +177,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-lse-variant", action="store_true",
                     help="skip the single-sweep figure (row normalisers supplied by the caller)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of a workload, measure what this GPU sustains for the scoring sweeps' "
+                         "instruction mix held in registers (MFMA alone, with softmax arithmetic, with LDS "
+                         "operand reads; random and zero operands) plus a library bf16 GEMM, and print them")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 "
                          "--pmc run of this command can scale its FETCH_SIZE / WRITE_SIZE readings")
@@ -155,6 +197,9 @@ def main() -> int:
     import paper_2506_08373_amd as S
     S.load_library()
     torch.cuda.set_device(0)
+    if args.ceilings:
+        print(json.dumps(_ceilings(S)))
+        return 0
     w = workloads.PRESETS[args.workload]()
     if args.layers > 0:
         w = dataclasses.replace(w, n_layers=args.layers, name="%s_%dlayers" % (w.name, args.layers))

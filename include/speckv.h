@@ -302,6 +302,17 @@ speckv_status specpc_compress_prompt(const speckv_params *p, int32_t l_skip, int
                                      int32_t *idx_out, int32_t *ids_out, int32_t *count_out,
                                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* Diagnostics: what this GPU sustains for the instruction mix of the scoring sweeps (Sec. 3.1
+ * Eq. 1 on MFMA score tiles) when nothing has to be fetched.  Launches one register-resident loop
+ * on `stream`: kind 0 = the bf16 MFMAs of 32x32 score tiles at d = 128 alone, 1 = with the softmax
+ * arithmetic of a tile (16 x (fma, exp2, add) per lane), 2 = as 1 with the B operands re-read from
+ * LDS (512 bytes per MFMA).  `operands` (device, 16-byte aligned, at least 64 KiB, read only)
+ * supplies the bf16 operand bits: random values and zeros draw very different power.  `out`
+ * (device, 512 KiB) receives one float per thread.  *flops (HOST) gets the matrix flops the
+ * launch executes; the caller times it.  Not part of the product path. */
+speckv_status speckv_probe_ceiling(int32_t kind, int32_t iters, const void *operands, void *out,
+                                   void *stream, int64_t *flops);
+
 #ifdef __cplusplus
 }
 #endif

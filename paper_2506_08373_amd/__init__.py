@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     load_library,
     n_keep,
     plan_info,
+    probe_ceiling,
     select_workspace_bytes,
     specpc_compress_prompt,
     specpc_compress_workspace_bytes,

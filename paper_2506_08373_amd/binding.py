@@ -49,7 +49,7 @@ EXPORTS = ("speckv_status_string", "speckv_n_keep", "speckv_total_keep", "speckv
            "specpc_workspace_bytes", "specpc_select_tokens", "specpc_compress_workspace_bytes",
            "specpc_compress_prompt", "speckv_ada_workspace_bytes", "speckv_select_ada",
            "speckv_compact_ada", "speckv_compress_ada", "speckv_plan_info", "speckv_compress_static",
-           "specpc_select_tokens_events", "speckv_select_workspace_bytes")
+           "specpc_select_tokens_events", "speckv_select_workspace_bytes", "speckv_probe_ceiling")
 
 
 def library_path() -> str:
@@ -118,6 +118,8 @@ def load_library() -> ctypes.CDLL:
     lib.specpc_compress_prompt.restype = ctypes.c_int
     lib.specpc_compress_prompt.argtypes = [P, ctypes.c_int32, ctypes.c_int32, vp, vp, i32p, i32p, i32p,
                                            i32p, vp, ctypes.c_size_t, vp]
+    lib.speckv_probe_ceiling.restype = ctypes.c_int
+    lib.speckv_probe_ceiling.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.POINTER(ctypes.c_int64)]
     _lib = lib
     return lib
 
@@ -349,7 +351,7 @@ def specpc_select_tokens_events(p: SpecKVParams, top_k: int, n_neighbor: int, q,
     _check(load_library().specpc_select_tokens_events(
         p.ref(), top_k, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
         _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
-        _ptr(count_out, torch.int32), wp, wb, _stream(), events, N_STAGE_EVENTS), "specpc_select_tokens_events", "speckv_select_workspace_bytes")
+        _ptr(count_out, torch.int32), wp, wb, _stream(), events, N_STAGE_EVENTS), "specpc_select_tokens_events")
 
 
 def specpc_compress_workspace_bytes(p: SpecKVParams, l_skip: int) -> int:
@@ -363,3 +365,13 @@ def specpc_compress_prompt(p: SpecKVParams, l_skip: int, n_neighbor: int, q, k, 
         p.ref(), l_skip, n_neighbor, _ptr(q, p.torch_dtype), _ptr(k, p.torch_dtype),
         _ptr(token_ids, torch.int32), _ptr(idx_out, torch.int32), _ptr(ids_out, torch.int32),
         _ptr(count_out, torch.int32), wp, wb, _stream()), "specpc_compress_prompt")
+
+
+def probe_ceiling(kind: int, iters: int, operands: torch.Tensor, out: torch.Tensor) -> int:
+    """Launches one ceiling-probe loop on the current stream; returns the matrix flops it executes."""
+    if operands.numel() * operands.element_size() < 65536 or out.numel() * out.element_size() < 512 * 1024:
+        raise ValueError("operands needs 64 KiB, out 512 KiB")
+    flops = ctypes.c_int64()
+    _check(load_library().speckv_probe_ceiling(kind, iters, _ptr(operands), _ptr(out, torch.float32), _stream(),
+                                               ctypes.byref(flops)), "speckv_probe_ceiling")
+    return int(flops.value)

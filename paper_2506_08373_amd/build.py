@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspeckv.so")
-SOURCES = ["api.hip", "score.hip", "score_qs.hip", "select.hip", "compact.hip"]
+SOURCES = ["api.hip", "score.hip", "score_qs.hip", "select.hip", "compact.hip", "probe.hip"]
 
 # Packed fp32 VALU ops are disabled on purpose; the host pass warns that it does not
 # know the feature, which is harmless.

@@ -1104,3 +1104,48 @@ def test_q_stationary_kernel_against_oracle_and_tile_kernel(S, monkeypatch):
         # which check_full_path has verified against the oracle; most rows agree exactly
         same = (idx_tile == idx_qs).all(axis=-1).mean() if idx_tile.ndim > 1 else float((idx_tile == idx_qs).all())
         assert (idx_tile == idx_qs).mean() > 0.98, (w.name, same)
+
+
+def test_token_selection_with_stage_events_matches_the_plain_call(S):
+    """`specpc_select_tokens_events` (the benchmark's timing variant) records its seven marks on the
+    launch stream and returns exactly what `specpc_select_tokens` returns."""
+    import ctypes
+    w = workloads.specpc_draft(n_in=5000, n_layers=3, name="pc_events")
+    t = workloads.generate(w)
+    q, k = t["q"].cuda(), t["k"].cuda()
+    ids = workloads.generate_token_ids(w).cuda()
+    p = make_params(S, w)
+    top_k, nb, n = 300, 4, w.seq_lens[0]
+    ws = torch.empty(S.specpc_workspace_bytes(p, top_k), dtype=torch.uint8, device="cuda")
+    outs = []
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(S.N_STAGE_EVENTS)]
+    for e in events:
+        e.record()                                   # creates the underlying HIP events
+    arr = (ctypes.c_void_p * S.N_STAGE_EVENTS)(*[e.cuda_event for e in events])
+    for timed in (False, True):
+        idx_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        ids_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        count = torch.zeros(1, dtype=torch.int32, device="cuda")
+        if timed:
+            S.specpc_select_tokens_events(p, top_k, nb, q, k, ids, idx_out, ids_out, count, ws, arr)
+        else:
+            S.specpc_select_tokens(p, top_k, nb, q, k, ids, idx_out, ids_out, count, ws)
+        torch.cuda.synchronize()
+        outs.append((idx_out, ids_out, count))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    assert int(outs[0][2].item()) > top_k
+    stage_ms = [events[i].elapsed_time(events[i + 1]) for i in range(S.N_STAGE_EVENTS - 1)]
+    assert all(ms >= 0.0 for ms in stage_ms) and sum(stage_ms) > 0.0
+
+
+def test_ceiling_probe_runs_and_reports_its_flops(S):
+    """The diagnostic loops behind `bench.py --ceilings` launch, finish and report the flops of the
+    launch: 256 workgroups x 8 waves x iters x 8 MFMAs of 32x32x16."""
+    ops = torch.randn(1 << 16, device="cuda").to(torch.bfloat16)
+    out = torch.full((256 * 512,), float("nan"), dtype=torch.float32, device="cuda")
+    for kind in (0, 1, 2):
+        flops = S.probe_ceiling(kind, 10, ops, out)
+        torch.cuda.synchronize()
+        assert flops == 256 * 8 * 10 * 8 * 32768
+        assert not bool(torch.isnan(out).any())
