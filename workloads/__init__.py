@@ -39,8 +39,9 @@ class SpecKVWorkload:
       ``channel_scale`` is set (mimics outlier channels), else 1.  The same scale
       multiplies K of that KV head and Q of the query heads in its group.
     * ``K = N(0,1) * scale``, ``V = N(0,1)``, ``Q = N(0,1) * scale * q_gain``.
-    * ``n_planted`` heavy-hitter keys per KV head: positions drawn without
-      replacement from the non-window prompt ``[0, n_in - n_window)``; each is
+    * ``n_planted`` heavy-hitter keys per KV head: one position drawn uniformly
+      from each of ``n_planted`` equal strata of the non-window prompt
+      ``[0, n_in - n_window)`` (distinct by construction); each is
       overwritten by ``3 * rho_g * q / ||q||`` for a random observation row ``q``
       of the group, ``rho_g`` being the RMS norm of that head's ordinary keys.
     * everything is rounded to ``dtype`` last.
@@ -208,7 +209,10 @@ def generate_layer_seq(w: SpecKVWorkload, layer: int, seq: int,
             raise ValueError("not enough non-window keys to plant heavy hitters")
         rho = k.pow(2).sum(-1).mean(0).sqrt()                     # [Hkv]
         for g in range(Hkv):
-            pos = torch.randperm(m, generator=gen, device=device)[: w.n_planted]
+            # one position per stratum of [0, m): distinct by construction, no sort needed
+            stride = m // w.n_planted
+            pos = (torch.arange(w.n_planted, device=device) * stride +
+                   torch.randint(0, stride, (w.n_planted,), generator=gen, device=device))
             rows = torch.randint(0, R, (w.n_planted,), generator=gen, device=device)
             heads = g * G + torch.randint(0, G, (w.n_planted,), generator=gen, device=device)
             qd = q[rows, heads]                                   # [P, d]
