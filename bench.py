@@ -82,7 +82,7 @@ def _scoring_kernel_symbol(S, p, w, stage: str) -> str:
     dt = {"bf16": 0, "f32": 1, "f16": 2}[w.dtype]
     npass = 1 if stage == "score_pass1" else 2
     red = info["reduce_max"] if npass == 2 else 0
-    if info["q_stationary"]:
+    if info["q_stationary"] & npass:
         return "score_qs_kernel<%d, %d, %d, %d>" % (dt, w.head_dim, npass, red)
     fn = "score_kernel_rows" if (npass == 1 and info["waves"] == 8) else "score_kernel_cols"
     return "%s<%d, %d, %d, %d, %d, %d, false>" % (fn, dt, w.head_dim, info["blocks_per_wave"], info["waves"],

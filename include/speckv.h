@@ -149,8 +149,9 @@ size_t speckv_workspace_bytes(const speckv_params *p);
  * info[0] waves per scoring workgroup, [1] 32-row blocks per wave, [2] row super-blocks per KV group,
  * [3] keys per chunk of the scoring sweeps, [4] unmasked chunks over all sequences, [5] keys per LDS
  * tile, [6] parts a row is split into for selection (1: one workgroup per row), [7] keys per such
- * part, [8] kernel of the unmasked scoring sweeps (0: key tiles streamed through LDS, 1: query
- * rows stationary in LDS), [9] 1 for max reduction.  Returns SPECKV_OK or the reason the
+ * part, [8] kernels of the unmasked scoring sweeps: bit 0 set when the row-statistics sweep, bit 1
+ * when the column-reduction sweep keeps the query rows stationary in LDS (clear: key tiles streamed
+ * through LDS), [9] 1 for max reduction.  Returns SPECKV_OK or the reason the
  * parameters are rejected. */
 #define SPECKV_PLAN_INFO_WORDS 10
 speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_INFO_WORDS]);

@@ -259,7 +259,7 @@ speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_
   info[0] = pl.g.NW; info[1] = pl.g.MB; info[2] = pl.g.RS; info[3] = pl.g.KC; info[4] = pl.g.n_fast_chunks;
   info[5] = rowb <= 128 ? 256 : rowb <= 256 ? 128 : 64;
   info[6] = pl.sel_parts; info[7] = pl.sel_part_len;
-  info[8] = score_uses_qs(pl) ? 1 : 0;
+  info[8] = (score_uses_qs(pl, 1) ? 1 : 0) | (score_uses_qs(pl, 2) ? 2 : 0);
   info[9] = pl.d.reduce_max;
   return SPECKV_OK;
 }

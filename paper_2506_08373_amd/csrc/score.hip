@@ -521,7 +521,7 @@ template <int DT, int D, int MB, int NW, int PASS, int RED>
 hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
   const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
   hipError_t e;
-  if (A.g.n_fast_chunks > 0 && qs_supported(A)) {
+  if (A.g.n_fast_chunks > 0 && qs_supported(A, PASS)) {
     if ((e = launch_qs_sweep(A, PASS, st)) != hipSuccess) return e;
   } else if (A.g.n_fast_chunks > 0) {
     const int64_t items = (int64_t)A.g.n_fast_chunks * A.d.L * A.d.Hkv;
@@ -587,11 +587,11 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
   return e;
 }
 
-bool score_uses_qs(const Plan &pl) {
+bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr;
-  return qs_supported(A);
+  return qs_supported(A, pass);
 }
 
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,

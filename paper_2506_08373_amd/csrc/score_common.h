@@ -92,7 +92,7 @@ struct Tile {
 // Returns false when the geometry is outside what that kernel is built for; then nothing was
 // launched and the caller uses the tile-streaming kernel.
 hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);   // score.hip
-bool qs_supported(const ScoreArgs &A);
+bool qs_supported(const ScoreArgs &A, int pass);
 hipError_t launch_qs_sweep(const ScoreArgs &A, int pass, hipStream_t st);
 
 }  // namespace speckv

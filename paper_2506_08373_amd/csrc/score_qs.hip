@@ -1,6 +1,7 @@
 // Scoring sweeps with the query rows stationary in LDS (Sec. 3.1 Eq. 1; Alg. 1 CrossAttention
 // and reduce steps; App. C.2 for the GQA group).  An alternative to the tile-streaming kernel of
-// score.hip for the unmasked chunks of large groups, selected with SPECKV_SCORE_KERNEL=qs.
+// score.hip for the unmasked chunks of large groups: by default it runs the row-statistics sweep at
+// d = 64; SPECKV_SCORE_KERNEL=qs selects it for every sweep it supports.
 //
 // Same mathematics (pass 1: per-row (reference, sum of exp2) over a chunk of keys; pass 2:
 // per-key sum over the rows of 2^(c*S - lse2)), different dataflow:
@@ -358,12 +359,22 @@ int qs_max_blocks(const ScoreArgs &A) {
 
 }  // namespace
 
-bool qs_supported(const ScoreArgs &A) {
-  // Opt-in: measured on the benchmark workloads this dataflow is not faster than the tile-streaming
-  // kernel (both end at the same matrix-pipe utilisation), so it only runs when the environment asks
-  // for it with SPECKV_SCORE_KERNEL=qs.  Read on every call so that a test can switch it.
+bool qs_supported(const ScoreArgs &A, int pass) {
+  // Default: only the row-statistics sweep at d = 64, where the vector pipe is the limit and this
+  // kernel's reference-exponent step (no maximum search) measures 12 % faster than the online step
+  // of the tile-streaming kernel.  Everywhere else the two dataflows end at the same matrix-pipe
+  // utilisation and the tile-streaming kernel is equal or slightly ahead.  The environment can
+  // override the choice: SPECKV_SCORE_KERNEL=tile (never), qs (both sweeps), qs1 / qs2 (that sweep
+  // only).  Read on every call so that a test can switch it.
   const char *e = std::getenv("SPECKV_SCORE_KERNEL");
-  if (e == nullptr || std::strcmp(e, "qs") != 0) return false;
+  bool want = pass == 1 && A.d.D == 64;
+  if (e != nullptr && e[0] != '\0') {
+    if (std::strcmp(e, "tile") == 0) want = false;
+    else if (std::strcmp(e, "qs") == 0) want = true;
+    else if (std::strcmp(e, "qs1") == 0) want = pass == 1;
+    else if (std::strcmp(e, "qs2") == 0) want = pass == 2;
+  }
+  if (!want) return false;
   if (A.d.dt == SPECKV_F32 || A.g.n_fast_chunks <= 0) return false;
   const int nb2 = qs_max_blocks(A);
   if (nb2 < kQsMinBlocks || nb2 * 32 > A.g.RSB) return false;

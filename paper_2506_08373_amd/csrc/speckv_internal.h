@@ -92,9 +92,10 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const in
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
                         float *planes, hipStream_t st, hipEvent_t *events = nullptr,
                         const float *lse_in = nullptr);
-// True when the unmasked chunks of this plan are swept by the Q-stationary kernel (score_qs.hip)
-// rather than the tile-streaming one (score.hip); diagnostics only.
-bool score_uses_qs(const Plan &pl);
+// True when sweep `pass` (1 row statistics, 2 column reduction) over the unmasked chunks of this
+// plan runs in the Q-stationary kernel (score_qs.hip) rather than the tile-streaming one
+// (score.hip); diagnostics only.
+bool score_uses_qs(const Plan &pl, int pass);
 // Row `lr` of super-block `rs` -> (head in group, observation row); false for padding rows.
 // Heads never share a 32-row block: each head's R rows are padded to Rp, and a super-block holds
 // either HPS whole heads or one of the PPH slices of a single head.

@@ -1091,12 +1091,15 @@ def test_q_stationary_kernel_against_oracle_and_tile_kernel(S, monkeypatch):
         t = workloads.generate(w)
         tg = {x: t[x].cuda() for x in ("q", "k", "v")}
         c_max = min(w.c_max, 256)
-        monkeypatch.delenv("SPECKV_SCORE_KERNEL", raising=False)
+        monkeypatch.setenv("SPECKV_SCORE_KERNEL", "tile")
         p = make_params(S, w, c_max=c_max, reduce=reduce)
         assert S.plan_info(p)["q_stationary"] == 0
         _, idx_tile, _, _ = run_compress(S, w, tg, c_max=c_max, reduce=reduce)
+        monkeypatch.delenv("SPECKV_SCORE_KERNEL", raising=False)
+        # default: only the row-statistics sweep at d = 64 keeps the query rows stationary
+        assert S.plan_info(p)["q_stationary"] == (1 if w.head_dim == 64 else 0)
         monkeypatch.setenv("SPECKV_SCORE_KERNEL", "qs")
-        assert S.plan_info(p)["q_stationary"] == 1, "the geometry of %s should be supported" % w.name
+        assert S.plan_info(p)["q_stationary"] == 3, "the geometry of %s should be supported" % w.name
         check_full_path(S, w, c_max=c_max, reduce=reduce)
         _, idx_qs, _, _ = run_compress(S, w, tg, c_max=c_max, reduce=reduce)
         monkeypatch.delenv("SPECKV_SCORE_KERNEL", raising=False)
@@ -1149,3 +1152,75 @@ def test_ceiling_probe_runs_and_reports_its_flops(S):
         torch.cuda.synchronize()
         assert flops == 256 * 8 * 10 * 8 * 32768
         assert not bool(torch.isnan(out).any())
+
+
+def test_token_selection_ignores_the_reduction_and_pooling_options(S):
+    """`specpc_select_tokens` is defined as sum aggregation with max pooling: parameters that ask for
+    max reduction or average pooling give the same tokens (rows above one workgroup's 512 rows, so
+    that a head spans several partial planes, the case where mixing the two would show)."""
+    base = workloads.specpc_draft(n_in=3000, n_layers=2, name="pc_ops")
+    w = workloads.SpecKVWorkload(**{**base.__dict__, "n_q_heads": 4, "n_kv_heads": 2, "n_window": 64,
+                                    "n_lookahead": 500})
+    t = workloads.generate(w)
+    q, k = t["q"].cuda(), t["k"].cuda()
+    ids = workloads.generate_token_ids(w).cuda()
+    top_k, nb, n = 200, 3, w.seq_lens[0]
+    outs = []
+    for reduce, pool in (("sum", "max"), ("max", "avg")):
+        p = make_params(S, w, reduce=reduce, pool=pool)
+        ws = torch.empty(S.specpc_workspace_bytes(p, top_k), dtype=torch.uint8, device="cuda")
+        idx_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        ids_out = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        count = torch.zeros(1, dtype=torch.int32, device="cuda")
+        S.specpc_select_tokens(p, top_k, nb, q, k, ids, idx_out, ids_out, count, ws)
+        torch.cuda.synchronize()
+        outs.append((idx_out, ids_out, count))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    ref = orc.specpc_select_tokens(workloads.to_float64(t["q"][:, 0]), workloads.to_float64(t["k"]),
+                                   ids.cpu().numpy(), w.n_window, w.pool_k, top_k, nb, w.sm_scale)
+    c = int(outs[0][2].item())
+    got = outs[0][0][:c].cpu().numpy().astype(np.int64)
+    m = n - w.n_window
+    if not np.array_equal(got, ref["idx"]):
+        tau = np.sort(ref["pooled"])[m - top_k]
+        band = REL_TOL * tau + ABS_FLOOR * ref["pooled"].max()
+        lo = orc.expand_neighbors(np.nonzero(ref["pooled"] > tau + band)[0], n, w.n_window, nb)
+        hi = orc.expand_neighbors(np.nonzero(ref["pooled"] >= tau - band)[0], n, w.n_window, nb)
+        assert np.isin(lo, got).all() and np.isin(got, hi).all()
+
+
+def test_more_than_65535_layer_head_units(S):
+    """Many layers times many KV heads: the launch grids put (layer, head) on the x dimension, which
+    has no 65535 limit."""
+    w = workloads.SpecKVWorkload(
+        name="many_units", n_layers=1100, n_q_heads=64, n_kv_heads=64, head_dim=64, seq_lens=(300,),
+        n_window=8, n_lookahead=8, pool_k=7, c_max=32, dtype="bf16", sm_scale=0.125, n_planted=2,
+        channel_scale=(0.5, 4.0), seed=41)
+    assert w.n_layers * w.n_kv_heads > 65535
+    t = workloads.generate(w, layers=range(3))                       # three distinct layers, tiled
+    reps = (w.n_layers + 2) // 3
+    q = t["q"].repeat(reps, 1, 1, 1, 1)[: w.n_layers].cuda()
+    k = t["k"].repeat(reps, 1, 1, 1)[: w.n_layers].cuda()
+    v = t["v"].repeat(reps, 1, 1, 1)[: w.n_layers].cuda()
+    p = make_params(S, w)
+    KT, L, H, d = S.total_keep(p), w.n_layers, w.n_kv_heads, w.head_dim
+    idx = torch.full((L, H * KT), -1, dtype=torch.int32, device="cuda")
+    k_out = torch.zeros((L, H * KT, d), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.zeros_like(k_out)
+    S.speckv_compress(p, q, k, v, idx, k_out, v_out, alloc_ws(S, p))
+    torch.cuda.synchronize()
+    # every third layer has the same inputs, so the same outputs; the first three against the oracle
+    idx3 = idx.view(L, H, KT)
+    for layer in range(3, L):
+        if layer % 97 == 0 or layer >= L - 3:
+            assert torch.equal(idx3[layer], idx3[layer % 3])
+            assert torch.equal(k_out[layer], k_out[layer % 3])
+    w3 = workloads.SpecKVWorkload(**{**w.__dict__, "n_layers": 3})
+    ref = oracle_batch(w3, t)
+    n = w.seq_lens[0]
+    got = idx3[:3].cpu().numpy()
+    for layer in range(3):
+        for g in range(H):
+            assert_indices_valid(got[layer, g], ref[layer][0]["pooled"][g], n, w.n_window, w.c_max,
+                                 "many units l%d g%d" % (layer, g))
