@@ -299,7 +299,7 @@ def main() -> int:
     dominant = max(("score_pass1", "score_pass2"), key=lambda n_: kernels[n_]["ms"])
     dk = kernels[dominant]
     traffic, traffic_src = (None, None) if tag is None else _traffic_from_profile(dominant, tag)
-    if d == 64:
+    if d == 64 and elt == 2:
         # at d = 64 a 32x32 score block costs half the matrix time of d = 128 but the same softmax
         # arithmetic: these sweeps are bound by the vector pipe, priced in plain (unpacked) fp32
         roofline = {"kernel": dk["kernel"], "stage": dominant, "bound": "alu", "achieved": dk["alu_TFLOPs"],
