@@ -784,14 +784,19 @@ def test_cascade_prompt_compression_then_cache_compression(S):
             assert np.array_equal(vo[layer, g], v64[layer][orig, g, :])
 
 
+@pytest.mark.parametrize("shape", ["8b_d128", "draft_d64"])
 @pytest.mark.parametrize("n_live", [7000, 4097, 3968, 1100, 300, 64])
-def test_device_side_token_count_equals_a_host_length_call(S, n_live):
+def test_device_side_token_count_equals_a_host_length_call(S, n_live, shape):
     """`n_in_dev`: the kernels read the number of live prompt tokens from device memory; the host
     length is only an upper bound.  Scores, indices and the compacted cache must equal those of a
     call whose host length is the live length (on the same first n_live tokens), with zeros / -1 in
     the slots a shorter prompt leaves unused."""
     n_cap = 7000
-    w = workloads.llama8b_layer(n_in=n_cap, c_max=512, n_layers=2, name="devlen")
+    if shape == "8b_d128":
+        w = workloads.llama8b_layer(n_in=n_cap, c_max=512, n_layers=2, name="devlen")
+    else:       # d = 64, 8 row blocks per group: the row-statistics sweep runs in the Q-stationary kernel
+        base = workloads.specpc_draft(n_in=n_cap, n_layers=2, name="devlen64")
+        w = workloads.SpecKVWorkload(**{**base.__dict__, "c_max": 512, "n_lookahead": 64})
     t = workloads.generate(w)
     q, k, v = (t[x].cuda() for x in ("q", "k", "v"))
     # the window rows of the live prompt are its last n_window tokens: only the key/value prefix matters
@@ -811,6 +816,8 @@ def test_device_side_token_count_equals_a_host_length_call(S, n_live):
         k_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
         v_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
         ws = alloc_ws(S, p)
+        if shape == "draft_d64" and name == "dev":
+            assert S.plan_info(p)["q_stationary"] == 1
         S.speckv_score(p, q, kk, pooled, raw, ws)
         S.speckv_compress(p, q, kk, vv, idx, k_out, v_out, ws)
         torch.cuda.synchronize()
