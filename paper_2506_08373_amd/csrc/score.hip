@@ -44,14 +44,14 @@ constexpr size_t score_lds_bytes() {
   return (size_t)2 * TL::TILE_BYTES + (size_t)2 * NW * MB * TL::KT * sizeof(float);
 }
 
-// One sweep over a chunk of keys.
+// One workgroup's sweep over a chunk of keys; bid = its index among the workgroups of its kind.
 //   PASS    1: row statistics, 2: column reduction
 //   RED     (pass 2) 0: sum over the rows of a head, 1: max over the rows of a head
 //   MASKED  false: every tile of the chunk is complete and visible to every row (key <= m), the
 //           loop body is straight-line code without any bounds or mask logic;
 //           true: the tail of a sequence (keys that window rows may not see, end of sequence)
 template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
-__device__ __forceinline__ void score_body(const ScoreArgs &A) {
+__device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   constexpr int ELT = elt_bytes(DT);
   using TL = Tile<ELT, D>;
   constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
@@ -68,15 +68,16 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   int unit, s, chunk, key_begin, key_end;
   if (MASKED) {
-    unit = blockIdx.x;
-    s = blockIdx.y;
+    const int units = d.L * d.Hkv * A.g.RS;
+    unit = bid % units;
+    s = bid / units;
     chunk = A.g.n_fast_chunks + s;
   } else {
     // 1-D grid.  Workgroups go to the 8 XCDs round-robin by their linear id and each XCD has its
     // own L2, so the RS row super-blocks that sweep the SAME keys of a (layer, head) get ids 8
     // apart: same XCD, dispatched together, and the keys come from HBM once instead of RS times.
     const int per_group = 8 * A.g.RS;
-    const int grp = blockIdx.x / per_group, within = blockIdx.x % per_group;
+    const int grp = bid / per_group, within = bid % per_group;
     const int item = grp * 8 + (within & 7);            // (layer, head, chunk), chunk fastest
     if (item >= A.g.n_fast_chunks * d.L * d.Hkv) return;
     chunk = item % A.g.n_fast_chunks;
@@ -433,16 +434,34 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A) {
 #undef SPECKV_LOAD_BFRAG
 #undef SPECKV_FLUSH_TILE
 
-// The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
-// then schedules its online-softmax step more freely); the column sweep does better without.
-template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_kernel_rows(ScoreArgs A) {
-  score_body<DT, D, MB, NW, PASS, RED, MASKED>(A);
+// A kernel with TAIL_ONLY = false is a whole sweep in one launch: its first A.tail_blocks
+// workgroups run the sequences' masked tails (one per (unit, sequence); the count is padded to a
+// multiple of 8 so that the chunk workgroups behind them keep their XCD assignment), the others one
+// unmasked chunk each.  The tails come first because they are short: their CUs are free again long
+// before the chunk workgroups run out.  TAIL_ONLY = true is the tails alone (calls without a
+// complete chunk, and the tails behind a Q-stationary sweep).
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool TAIL_ONLY>
+__device__ __forceinline__ void score_dispatch(const ScoreArgs &A) {
+  const int bid = blockIdx.x;
+  if (TAIL_ONLY) {
+    score_body<DT, D, MB, NW, PASS, RED, true>(A, bid);
+  } else if (bid < A.tail_blocks) {
+    if (bid < A.d.L * A.d.Hkv * A.g.RS * A.d.S) score_body<DT, D, MB, NW, PASS, RED, true>(A, bid);
+  } else {
+    score_body<DT, D, MB, NW, PASS, RED, false>(A, bid - A.tail_blocks);
+  }
 }
 
-template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
+// The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
+// then schedules its online-softmax step more freely); the column sweep does better without.
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool TAIL_ONLY>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_kernel_rows(ScoreArgs A) {
+  score_dispatch<DT, D, MB, NW, PASS, RED, TAIL_ONLY>(A);
+}
+
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool TAIL_ONLY>
 __global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
-  score_body<DT, D, MB, NW, PASS, RED, MASKED>(A);
+  score_dispatch<DT, D, MB, NW, PASS, RED, TAIL_ONLY>(A);
 }
 
 // Merges the per-chunk (max2, sum) pairs of each row into lse2 = max2 + log2(sum).
@@ -518,21 +537,26 @@ hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_
 }
 
 template <int DT, int D, int MB, int NW, int PASS, int RED>
-hipError_t launch_sweep(const ScoreArgs &A, size_t lds, hipStream_t st) {
-  const unsigned units = A.d.L * A.d.Hkv * A.g.RS;
-  hipError_t e;
-  if (A.g.n_fast_chunks > 0 && qs_supported(A, PASS)) {
-    if ((e = launch_qs_sweep(A, PASS, st)) != hipSuccess) return e;
-  } else if (A.g.n_fast_chunks > 0) {
+hipError_t launch_sweep(const ScoreArgs &A0, size_t lds, hipStream_t st) {
+  ScoreArgs A = A0;
+  const int64_t tails = (int64_t)A.d.L * A.d.Hkv * A.g.RS * A.d.S;
+  if (tails > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 block(NW * 64);
+  A.tail_blocks = 0;
+  if (A.g.n_fast_chunks > 0 && !qs_supported(A, PASS)) {
     const int64_t items = (int64_t)A.g.n_fast_chunks * A.d.L * A.d.Hkv;
-    const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS;
+    A.tail_blocks = (int)((tails + 7) / 8 * 8);
+    const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS + A.tail_blocks;
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs), block(NW * 64);
-    if (PASS == 1 && NW == 8) e = launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
-    else e = launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    const dim3 grid((unsigned)wgs);
+    if (PASS == 1 && NW == 8) return launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+  }
+  if (A.g.n_fast_chunks > 0) {
+    const hipError_t e = launch_qs_sweep(A, PASS, st);
     if (e != hipSuccess) return e;
   }
-  return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, true>, A, dim3(units, A.d.S), dim3(NW * 64), lds, st);
+  return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, true>, A, dim3((unsigned)tails), block, lds, st);
 }
 
 template <int DT, int D, int MB, int NW>
@@ -590,7 +614,7 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
 bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
-  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr;
+  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.tail_blocks = 0;
   return qs_supported(A, pass);
 }
 
@@ -599,7 +623,7 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
-  A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in;
+  A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in; A.tail_blocks = 0;
   switch (pl.d.dt) {
     case SPECKV_BF16: return pl.d.D == 128 ? dispatch_geom<kBf16, 128>(A, st, events) : dispatch_geom<kBf16, 64>(A, st, events);
     case SPECKV_F16: return pl.d.D == 128 ? dispatch_geom<kF16, 128>(A, st, events) : dispatch_geom<kF16, 64>(A, st, events);

@@ -18,6 +18,7 @@ struct ScoreArgs {
   float *lse;       // [layer][head][seq][RS*RSB]
   const float *lse_in;   // optional caller-supplied natural-log normalisers [L][S][R][Hq]
   float *planes;    // [RS][layer][Hkv*T]
+  int tail_blocks;  // whole-sweep launches: leading workgroups that run the masked tails (multiple of 8)
 };
 
 namespace {
