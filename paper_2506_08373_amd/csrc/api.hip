@@ -183,6 +183,12 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
       pl->off_sel_state = take((size_t)rows * (2 + 2 * (size_t)pl->sel_parts) * sizeof(uint32_t));
     }
   }
+  // first-digit histograms of the pooled rows for the one-workgroup selection of the fused calls
+  pl->off_hist0 = 0; pl->hist0_words = 0;
+  if (!one_row_per_call && pl->sel_parts == 1) {
+    pl->hist0_words = (int64_t)d.L * d.S * d.Hkv * 2048;
+    pl->off_hist0 = take((size_t)pl->hist0_words * sizeof(uint32_t));
+  }
   pl->total = off;
   pl->off_ada_hist = take((size_t)d.L * d.S * d.Hkv * 2048 * sizeof(uint32_t));
   pl->off_ada_state = take((size_t)d.L * d.S * (2 + 3 * (size_t)d.Hkv) * sizeof(uint32_t));
@@ -365,13 +371,16 @@ static speckv_status compress_impl(const speckv_params *p, const void *q, const 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   float *planes = reinterpret_cast<float *>(ws + pl.off_planes);
   float *pooled = reinterpret_cast<float *>(ws + pl.off_pooled);
+  // the pooling kernel also counts the first selection digit of every row (counters zeroed by the
+  // kernel between the sweeps), so that selection starts at its second read of the pooled scores
+  uint32_t *hist0 = pl.hist0_words > 0 ? reinterpret_cast<uint32_t *>(ws + pl.off_hist0) : nullptr;
   hipError_t e = launch_score(pl, q, k, reinterpret_cast<float2 *>(ws + pl.off_part),
-                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev, lse_in);
+                              reinterpret_cast<float *>(ws + pl.off_lse), planes, hs, ev, lse_in, hist0, pl.hist0_words);
   if (e != hipSuccess) return SPECKV_ERR_RUNTIME;
-  if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+  if ((e = launch_reduce_pool(pl, planes, nullptr, pooled, hs, hist0)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_select(pl, pooled, idx, reinterpret_cast<uint32_t *>(ws + pl.off_sel_hist),
-                         reinterpret_cast<uint32_t *>(ws + pl.off_sel_state), hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
+                         reinterpret_cast<uint32_t *>(ws + pl.off_sel_state), hs, hist0)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[5], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if ((e = launch_compact(pl, k, v, idx, k_out, v_out, hs)) != hipSuccess) return SPECKV_ERR_RUNTIME;
   if (ev && hipEventRecord(ev[6], hs) != hipSuccess) return SPECKV_ERR_RUNTIME;

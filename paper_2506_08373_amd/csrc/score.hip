@@ -468,6 +468,14 @@ __global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
 // A block covers 64 rows; its 4 waves split the chunks and merge their partial pairs in LDS.
 constexpr int kMergeRows = 64, kMergeSlices = 4;
 
+// Zeroes A.clear (if any), the work spread over every thread of the grid.
+__device__ inline void clear_scratch(const ScoreArgs &A) {
+  if (A.clear == nullptr) return;
+  const int64_t n_threads = (int64_t)gridDim.x * gridDim.y * blockDim.x;
+  const int64_t id = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+  for (int64_t i = id; i < A.clear_words; i += n_threads) A.clear[i] = 0u;
+}
+
 __device__ inline void merge_pair(float &m, float &l, float m2, float l2) {
   const float mm = fmaxf(m, m2);
   l = l * exp2f(m - mm) + l2 * exp2f(m2 - mm);
@@ -475,6 +483,7 @@ __device__ inline void merge_pair(float &m, float &l, float m2, float l2) {
 }
 
 __global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(ScoreArgs A) {
+  clear_scratch(A);
   __shared__ float2 partial[kMergeSlices][kMergeRows];
   const Dims &d = A.d;
   const int RSB = A.g.RSB;
@@ -512,6 +521,7 @@ __global__ __launch_bounds__(kMergeRows * kMergeSlices) void lse_combine_kernel(
 // Converts caller-supplied natural-log normalisers [L][S][R][Hq] into the padded log2 layout
 // the column-reduction sweep reads.
 __global__ __launch_bounds__(256) void lse_import_kernel(ScoreArgs A) {
+  clear_scratch(A);
   const Dims &d = A.d;
   const int RSB = A.g.RSB;
   const int unit = blockIdx.x;            // (layer, head, row super-block)
@@ -614,16 +624,18 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
 bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
-  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.tail_blocks = 0;
+  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.tail_blocks = 0; A.clear = nullptr; A.clear_words = 0;
   return qs_supported(A, pass);
 }
 
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
-                        float *planes, hipStream_t st, hipEvent_t *events, const float *lse_in) {
+                        float *planes, hipStream_t st, hipEvent_t *events, const float *lse_in,
+                        uint32_t *clear, int64_t clear_words) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
   A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in; A.tail_blocks = 0;
+  A.clear = clear; A.clear_words = clear != nullptr ? clear_words : 0;
   switch (pl.d.dt) {
     case SPECKV_BF16: return pl.d.D == 128 ? dispatch_geom<kBf16, 128>(A, st, events) : dispatch_geom<kBf16, 64>(A, st, events);
     case SPECKV_F16: return pl.d.D == 128 ? dispatch_geom<kF16, 128>(A, st, events) : dispatch_geom<kF16, 64>(A, st, events);

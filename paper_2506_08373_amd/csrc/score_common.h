@@ -18,6 +18,8 @@ struct ScoreArgs {
   float *lse;       // [layer][head][seq][RS*RSB]
   const float *lse_in;   // optional caller-supplied natural-log normalisers [L][S][R][Hq]
   float *planes;    // [RS][layer][Hkv*T]
+  uint32_t *clear;  // optional scratch the kernel between the sweeps zeroes (clear_words words)
+  int64_t clear_words;
   int tail_blocks;  // whole-sweep launches: leading workgroups that run the masked tails (multiple of 8)
 };
 
@@ -92,7 +94,6 @@ struct Tile {
 // rows stationary in LDS and each wave streaming its own keys through registers (score_qs.hip).
 // Returns false when the geometry is outside what that kernel is built for; then nothing was
 // launched and the caller uses the tile-streaming kernel.
-hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);   // score.hip
 bool qs_supported(const ScoreArgs &A, int pass);
 hipError_t launch_qs_sweep(const ScoreArgs &A, int pass, hipStream_t st);
 

@@ -5,11 +5,14 @@
 //    kernel k over the non-window candidates (Alg. 1 pooling step; table: Max, k = 7).
 //  * select: the C largest pooled scores per (layer, sequence, KV head), ties to the
 //    smaller index, ascending, then the window m..n_in-1 (Alg. 1 "Select KVs").
-//    MSD radix select on order-preserving 32-bit keys (11 + 11 + 10 bits, LDS
-//    histograms), then an ordered compaction that ranks candidates with wavefront
-//    prefix sums.  One workgroup per row; every step is deterministic.  A workgroup is
-//    bound by its vector ALU, so the per-element work is kept minimal: 128-bit loads,
-//    digits taken from the raw float bits, float compares against the threshold.
+//    MSD radix select on order-preserving 32-bit keys (digits of 11 + 11 + 10 bits).  One
+//    workgroup per row; every step is deterministic.  The histogram of the first digit comes
+//    from the pooling kernel in the fused calls (else from one read of the row); rows of up to
+//    about 229K entries are then read once more: entries above the threshold's bin are
+//    selected outright, the few inside it settle the other two digits in LDS.  Longer rows, and
+//    rows with more than 4096 entries in that bin, take one read per digit plus an ordered
+//    compaction.  A workgroup is bound by its vector ALU, so the per-element work is kept
+//    minimal: 128-bit loads, float compares against the bin's bounds, digits from raw bits.
 //  * shared layer budget: per-head counts from one layer-wide threshold (histogram and
 //    decision kernels per digit), then the same row select with each head's own count.
 //  * expand: widens selected tokens to +-n_neighbor, unites them with the window and
@@ -18,6 +21,15 @@
 
 namespace speckv {
 namespace {
+
+// Raw bits of x with -0 turned into +0 (the two compare equal and must share a bin).
+__device__ __forceinline__ uint32_t raw_bits(float x) { return __float_as_uint(x + 0.0f); }
+// Ordered key of a float (larger float, larger key): key = u | 0x80000000 for a positive number
+// with bits u and ~u for a negative one.  The selection works on digits of this key.
+__device__ __forceinline__ uint32_t ordered_key(float x) {
+  const uint32_t u = raw_bits(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
 
 // ----------------------------------------------------------------------------------
 // reduce + pool
@@ -37,7 +49,7 @@ struct PlaneMerge {
 __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge pm,
                                         float *__restrict__ raw, float *__restrict__ pooled,
                                         int n_s, int n_row, int m, int pool_k, int pool_avg, int j0,
-                                        float *tile) {
+                                        float *tile, uint32_t *first_digit = nullptr) {
   // window of key j: j - half .. j + after (symmetric for odd kernels; an even kernel looks one
   // position further back than ahead, the library convention with padding k / 2)
   const int half = pool_k / 2, after = (pool_k - 1) / 2;
@@ -74,6 +86,7 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge
       } else {
         for (int jj = lo + 1; jj <= hi; ++jj) best = fmaxf(best, tile[jj - j0 + half]);
       }
+      if (first_digit != nullptr) atomicAdd(&first_digit[ordered_key(best) >> 21], 1u);   // selection's first digit
     }
     pooled[j] = best;
   }
@@ -81,8 +94,9 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge
 
 __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
     Dims d, SeqTab t, PlaneMerge pm, const float *__restrict__ planes,
-    float *__restrict__ raw, float *__restrict__ pooled, int tiles_per_row) {
+    float *__restrict__ raw, float *__restrict__ pooled, int tiles_per_row, uint32_t *__restrict__ hist0) {
   __shared__ float tile[kPoolTile + SPECKV_MAX_POOL_K + 1];
+  __shared__ uint32_t first_digit[2048];
   const int unit = blockIdx.x / tiles_per_row;
   const int j0 = (blockIdx.x - unit * tiles_per_row) * kPoolTile;
   const int g = unit % d.Hkv;
@@ -92,8 +106,19 @@ __global__ __launch_bounds__(kPoolThreads) void reduce_pool_kernel(
   if (j0 >= n_row) return;
   const int n_s = live_len(d, t, s);
   const int64_t base = (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_row;
+  // with hist0: the tile's histogram of the first selection digit is built in LDS (cleared here; the
+  // barrier inside reduce_pool_tile orders the clearing before the counting) and added to the row's
+  if (hist0 != nullptr)
+    for (int b = threadIdx.x; b < 2048; b += kPoolThreads) first_digit[b] = 0;
   reduce_pool_tile(planes + base, pm, raw ? raw + base : nullptr, pooled + base, n_s, n_row, n_s - d.w,
-                   d.pool_k, d.pool_avg, j0, tile);
+                   d.pool_k, d.pool_avg, j0, tile, hist0 != nullptr ? first_digit : nullptr);
+  if (hist0 != nullptr) {
+    __syncthreads();
+    for (int b = threadIdx.x; b < 2048; b += kPoolThreads) {
+      const uint32_t c = first_digit[b];
+      if (c != 0) atomicAdd(&hist0[(int64_t)unit * 2048 + b], c);
+    }
+  }
 }
 
 // One output row that merges every plane (all layers, heads, row super-blocks) of a
@@ -178,25 +203,39 @@ __device__ __forceinline__ int raw_digit(int D, int pass, int nb, bool neg) {
 __device__ __forceinline__ uint32_t raw_prefix_of(uint32_t prefix, uint32_t mask) {
   return (prefix & 0x80000000u) ? (prefix ^ 0x80000000u) : (~prefix & mask);
 }
-// Raw bits of x with -0 turned into +0 (the two compare equal and must share a bin).
-__device__ __forceinline__ uint32_t raw_bits(float x) { return __float_as_uint(x + 0.0f); }
 
 struct SelShared {
   uint32_t hist[kHistCopies * 2048];   // one copy per lane residue: spreads atomics that hit one bin
   uint32_t wave_tot[2][kSelWaves];
-  uint32_t prefix, remaining;
+  uint32_t prefix, remaining, bin_count;
 };
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves:
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add 0), then lane 15 of
+// rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  int x = (int)v;
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return (uint32_t)x;
+}
+
+// Exclusive prefix sum of v over the wavefront; *total gets the sum.
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, uint32_t *total) {
+  const uint32_t inc = wave_inclusive_scan(v);
+  *total = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+  return inc - v;
+}
+
 // Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
-// Uses wavefront shuffles for the in-wave scan and LDS for the 16 wave totals.
+// Wavefront scans, then LDS for the 16 wave totals.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *wave_tot, uint32_t *total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t up = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += up;
-  }
+  const uint32_t inc = wave_inclusive_scan(v);
   if (lane == 63) wave_tot[wave] = inc;
   __syncthreads();
   uint32_t before = 0, all = 0;
@@ -256,45 +295,51 @@ __device__ __forceinline__ void histogram_pass(const float *__restrict__ x, int 
   __syncthreads();
 }
 
-// Ordered key of the count-th largest entry of x[0..m) (1 <= count <= m) and how many of the
-// entries equal to it belong to the `count` largest.
-__device__ __forceinline__ void radix_threshold(const float *__restrict__ x, int m, RowSplit rs, int count,
-                                                SelShared &sh, uint32_t *thr_key, uint32_t *need_eq_out) {
+// c0, c1: this thread's counts of the entries with digit nb-1-2t and nb-2-2t (ordered digits of
+// level `pass`, t the thread) among the entries that share `prefix`.  Extends `prefix` by the digit
+// that holds the remaining-th largest of them, reduces `remaining` to its rank among the entries
+// with that digit and returns how many entries have it.
+__device__ __forceinline__ uint32_t decide_from_counts(SelShared &sh, int pass, uint32_t c0, uint32_t c1,
+                                                       uint32_t &prefix, uint32_t &mask, uint32_t &remaining) {
   const int tid = threadIdx.x;
-  uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
-#pragma unroll
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 21 : pass == 1 ? 10 : 0;       // digits of 11, 11 and 10 bits
-    const int nb = pass == 2 ? 1024 : 2048;
-    histogram_pass(x, m, rs, prefix, mask, shift, nb, sh);
-    // thread t owns the bins nb-1-2t and nb-2-2t: scanning threads in order walks the
-    // bins from the largest digit down.
-    const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
-    const bool neg = (prefix & 0x80000000u) == 0;
-    const int r0 = raw_digit(b0, pass, nb, neg), r1 = raw_digit(b1, pass, nb, neg);
-    uint32_t c0 = 0, c1 = 0;
-#pragma unroll
-    for (int cp = 0; cp < kHistCopies; ++cp) {
-      if (b0 >= 0) c0 += sh.hist[cp * 2048 + r0];
-      if (b1 >= 0) c1 += sh.hist[cp * 2048 + r1];
-    }
-    uint32_t total;
-    const uint32_t above = block_exclusive_scan(c0 + c1, sh.wave_tot[0], &total);
-    if (above < remaining && remaining <= above + c0) {
-      sh.prefix = prefix | ((uint32_t)b0 << shift);
-      sh.remaining = remaining - above;
-    } else if (above + c0 < remaining && remaining <= above + c0 + c1) {
-      sh.prefix = prefix | ((uint32_t)b1 << shift);
-      sh.remaining = remaining - above - c0;
-    }
-    __syncthreads();
-    prefix = sh.prefix;
-    remaining = sh.remaining;
-    mask |= (uint32_t)(nb - 1) << shift;
-    __syncthreads();
+  const int shift = pass == 0 ? 21 : pass == 1 ? 10 : 0;       // digits of 11, 11 and 10 bits
+  const int nb = pass == 2 ? 1024 : 2048;
+  const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;      // scanning threads in order walks the bins downwards
+  uint32_t total;
+  const uint32_t above = block_exclusive_scan(c0 + c1, sh.wave_tot[0], &total);
+  if (above < remaining && remaining <= above + c0) {
+    sh.prefix = prefix | ((uint32_t)b0 << shift);
+    sh.remaining = remaining - above;
+    sh.bin_count = c0;
+  } else if (above + c0 < remaining && remaining <= above + c0 + c1) {
+    sh.prefix = prefix | ((uint32_t)b1 << shift);
+    sh.remaining = remaining - above - c0;
+    sh.bin_count = c1;
   }
-  *thr_key = prefix;
-  *need_eq_out = remaining;
+  __syncthreads();
+  prefix = sh.prefix;
+  remaining = sh.remaining;
+  const uint32_t in_bin = sh.bin_count;
+  mask |= (uint32_t)(nb - 1) << shift;
+  __syncthreads();
+  return in_bin;
+}
+
+// The same after histogram_pass for digit `pass`: the counts come from the LDS histogram.
+__device__ __forceinline__ uint32_t decide_digit(SelShared &sh, int pass, uint32_t &prefix, uint32_t &mask,
+                                                 uint32_t &remaining) {
+  const int tid = threadIdx.x;
+  const int nb = pass == 2 ? 1024 : 2048;
+  const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+  const bool neg = (prefix & 0x80000000u) == 0;
+  const int r0 = raw_digit(b0, pass, nb, neg), r1 = raw_digit(b1, pass, nb, neg);
+  uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+  for (int cp = 0; cp < kHistCopies; ++cp) {
+    if (b0 >= 0) c0 += sh.hist[cp * 2048 + r0];
+    if (b1 >= 0) c1 += sh.hist[cp * 2048 + r1];
+  }
+  return decide_from_counts(sh, pass, c0, c1, prefix, mask, remaining);
 }
 
 // Writes, ascending, the indices of the entries of x[0..m) above the threshold key and of the
@@ -346,16 +391,13 @@ __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m
       // (a tile holds at most 16384 entries, so neither field can overflow)
       uint32_t total;
       const uint32_t before = block_exclusive_scan(cg | (ce << 16), sh.wave_tot[buf], &total);
-      uint32_t gt_before = run_gt + (before & 0xffffu), eq_before = run_eq + (before >> 16);
-      if ((gt_bits | eq_bits) != 0) {
-#pragma unroll
-        for (int b = 0; b < 4 * kSelVec; ++b) {
-          const bool is_gt = (gt_bits >> b) & 1u, is_eq = (eq_bits >> b) & 1u;
-          if (is_gt || (is_eq && eq_before < need_eq))
-            out[gt_before + min(eq_before, need_eq)] = index_base + rs.lead + 4 * vb + b;
-          gt_before += is_gt;
-          eq_before += is_eq;
-        }
+      const uint32_t gt_before = run_gt + (before & 0xffffu), eq_before = run_eq + (before >> 16);
+      // selected entries are rare: only the set bits are visited
+      for (uint32_t rest = gt_bits | eq_bits; rest != 0; rest &= rest - 1) {
+        const int b = __ffs(rest) - 1;
+        const uint32_t below = (1u << b) - 1u;
+        const uint32_t gt_b = gt_before + __popc(gt_bits & below), eq_b = eq_before + __popc(eq_bits & below);
+        if (((gt_bits >> b) & 1u) || eq_b < need_eq) out[gt_b + min(eq_b, need_eq)] = index_base + rs.lead + 4 * vb + b;
       }
       run_gt += total & 0xffffu;
       run_eq += total >> 16;
@@ -372,20 +414,331 @@ __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m
   }
 }
 
+// ---- rows of up to kFastMaxVec vectors: one more read after the first digit ----
+// Once the first digit is decided the threshold's bin is known.  Entries in higher bins are
+// selected whatever the other digits turn out to be ("winners"); only the entries of that bin
+// ("candidates", usually a small fraction of the row) decide the rest of the threshold.  So the
+// row is read just once more:
+//   1. every wavefront classifies a contiguous part of the row, tile by tile, and leaves per thread
+//      and tile a word of winner and candidate bits in LDS - no scans, no barriers;
+//   2. after one exchange of the wavefronts' totals each wavefront walks its words again (LDS only),
+//      turns the bit counts into positions with wavefront scans and appends its candidates to an
+//      LDS list in index order (ordered key, index, winners before);
+//   3. the remaining 21 bits of the threshold are found on that list;
+//   4. every output position follows from counts that are already there:
+//        a selected candidate goes to  (winners before it) + (selected candidates before it),
+//        a winner to                   (winners before it) + (selected candidates with a smaller index).
+//      For the latter the selected candidates are counted per range (the entries one wavefront holds
+//      in one tile: consecutive indices); a winner adds the ranges before its own and searches the
+//      few selected candidates of its own range.
+constexpr int kFastSlots = 16;                                   // per wavefront: leading scalars, 14 tiles, trailing scalars
+constexpr int kWaveTileVec = 64 * kSelVec;                       // 128-bit vectors per wavefront tile
+constexpr int kFastMaxVec = (kFastSlots - 2) * kWaveTileVec * kSelWaves;
+constexpr int kFastRanges = kFastSlots * kSelWaves;
+constexpr int kCandCap = 4096;                                   // candidates the LDS list holds
+
+struct FastShared {
+  uint32_t marks[kFastSlots][kSelThreads + 1];   // per thread and slot: winner bits (low 16) and candidate bits, later
+                                                 // winner bits and the winners before them in the wavefront's part
+                                                 // (rows padded by one word: step 2 reads across slots)
+  uint32_t ckey[kCandCap];                    // candidates in index order: ordered key (later: indices of the
+                                              //   selected candidates, ascending),
+  int32_t cidx[kCandCap];                     //   index in the row,
+  uint32_t cgtb[kCandCap];                    //   winners before it (low 24 bits), its range (high 8 bits)
+  uint32_t hist[2048];
+  uint32_t range_sel[kFastRanges + 1];        // selected candidates before each range (wavefront-major)
+  uint32_t wave_cnt[kSelWaves];               // winners (low 16 bits) and candidates per wavefront
+  uint32_t wave_tot[2][kSelWaves];
+  uint32_t found[2];
+};
+constexpr size_t kSelLdsBytes = sizeof(FastShared) > sizeof(SelShared) ? sizeof(FastShared) : sizeof(SelShared);
+
+// Smallest and largest float of first-digit bin `bin` (ordered digit).  Bins that hold NaN
+// patterns are cut at the infinities, and the bin just below zero ends at the largest negative
+// number (zero of either sign belongs to the bin above).
+__device__ __forceinline__ void bin_bounds(uint32_t bin, float *lo, float *hi) {
+  if (bin >= 1024u) {
+    const uint32_t base = (bin - 1024u) << 21;
+    *lo = __uint_as_float(min(base, 0x7f800000u));
+    *hi = __uint_as_float(min(base | 0x1fffffu, 0x7f800000u));
+  } else {
+    const uint32_t base = (2047u - bin) << 21;                  // sign bit set
+    *lo = __uint_as_float(min(base | 0x1fffffu, 0xff800000u));
+    *hi = __uint_as_float(min(max(base, 0x80000001u), 0xff800000u));
+  }
+}
+
+// The `take` largest entries of first-digit bin `bin` plus every entry of a higher bin, indices
+// ascending, ties to the lower index (see above).  rs.nv <= kFastMaxVec and at most kCandCap
+// entries in the bin.
+__device__ __forceinline__ void select_after_first_digit(const float *__restrict__ x, int m, RowSplit rs,
+                                                         uint32_t bin, uint32_t take,
+                                                         int32_t *__restrict__ out, FastShared &fs) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float lo_f, hi_f;
+  bin_bounds(bin, &lo_f, &hi_f);
+  // the wavefront's part of the vectors: whole tiles, the same number for every wavefront
+  const int part_vec = ((rs.nv + kSelWaves - 1) / kSelWaves + kWaveTileVec - 1) / kWaveTileVec * kWaveTileVec;
+  const int v_begin = min(wv * part_vec, rs.nv), v_end = min(v_begin + part_vec, rs.nv);
+  const int n_tiles = (v_end - v_begin + kWaveTileVec - 1) / kWaveTileVec;
+  const bool has_lead = wv == 0 && rs.lead > 0, has_tail = wv == kSelWaves - 1 && m > rs.tail0;
+  // row index of bit 0 of the word of lane `ln` of this wavefront in a slot
+  auto index0 = [&](int slot, int ln) {
+    if (slot == 0) return ln;
+    if (slot == kFastSlots - 1) return rs.tail0 + ln;
+    return rs.lead + 4 * (v_begin + (slot - 1) * kWaveTileVec + ln * kSelVec);
+  };
+
+  // ---- 1. classification
+  uint32_t mine = 0;                            // this thread's winners (low 16 bits) and candidates
+  auto classify_scalar = [&](int slot, int first, int n) {
+    uint32_t w = 0;
+    if (lane < n) {
+      const float xv = x[first + lane];
+      w = (xv > hi_f ? 1u : 0u) | ((xv >= lo_f && xv <= hi_f) ? 1u << 16 : 0u);
+    }
+    fs.marks[slot][tid] = w;
+    mine += w;
+  };
+  if (has_lead) classify_scalar(0, 0, rs.lead);
+  if (n_tiles > 0) {
+    // the values of the next tile are requested before the current tile is classified
+    const float4 *xv = reinterpret_cast<const float4 *>(x + rs.lead);
+    float4 val[kSelVec], nxt[kSelVec];
+#pragma unroll
+    for (int e = 0; e < kSelVec; ++e) val[e] = xv[min(v_begin + lane * kSelVec + e, rs.nv - 1)];
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      const int vb = v_begin + tile * kWaveTileVec + lane * kSelVec;
+#pragma unroll
+      for (int e = 0; e < kSelVec; ++e) nxt[e] = xv[min(vb + kWaveTileVec + e, rs.nv - 1)];
+      uint32_t gt_bits = 0, ge_bits = 0;
+#pragma unroll
+      for (int e = 0; e < kSelVec; ++e) {
+        const float e4[4] = {val[e].x, val[e].y, val[e].z, val[e].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          gt_bits |= e4[c] > hi_f ? 1u << (4 * e + c) : 0u;
+          ge_bits |= e4[c] >= lo_f ? 1u << (4 * e + c) : 0u;
+        }
+      }
+      const int n_valid = min(max(v_end - vb, 0), kSelVec);                 // vectors of this thread inside the part
+      const uint32_t valid = (1u << (4 * n_valid)) - 1u;
+      gt_bits &= valid;
+      const uint32_t c_bits = ge_bits & ~gt_bits & valid;
+      fs.marks[1 + tile][tid] = gt_bits | (c_bits << 16);
+      mine += __popc(gt_bits) | (__popc(c_bits) << 16);
+#pragma unroll
+      for (int e = 0; e < kSelVec; ++e) val[e] = nxt[e];
+    }
+  }
+  if (has_tail) classify_scalar(kFastSlots - 1, rs.tail0, m - rs.tail0);
+  // a part holds fewer than 2^16 entries, so the packed counts cannot overflow
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
+  if (lane == 0) fs.wave_cnt[wv] = mine;
+  for (int b = tid; b <= kFastRanges; b += kSelThreads) fs.range_sel[b] = 0;
+  __syncthreads();
+  uint32_t gt_base = 0, c_base = 0, c_all = 0;   // winners / candidates before this wavefront's part; all candidates
+#pragma unroll
+  for (int w2 = 0; w2 < kSelWaves; ++w2) {
+    const uint32_t v = fs.wave_cnt[w2];
+    if (w2 < wv) { gt_base += v & 0xffffu; c_base += v >> 16; }
+    c_all += v >> 16;
+  }
+
+  // ---- 2. positions inside the wavefront's part; candidates to the list (their keys follow)
+  {
+    uint32_t run_gt = 0, run_c = c_base;
+    // one word of lane `ln`: the winners before it become its upper half, its candidates are listed
+    auto place_word = [&](int slot, int ln, uint32_t g_before, uint32_t c_before) {
+      const uint32_t w = fs.marks[slot][wv * 64 + ln];
+      const uint32_t gt_bits = w & 0xffffu, c_bits = w >> 16;
+      fs.marks[slot][wv * 64 + ln] = gt_bits | (g_before << 16);
+      for (uint32_t rest = c_bits; rest != 0; rest &= rest - 1) {          // candidates are few
+        const int b = __ffs(rest) - 1;
+        const uint32_t below = (1u << b) - 1u;
+        const uint32_t cpos = c_before + __popc(c_bits & below);
+        if (cpos < (uint32_t)kCandCap) {
+          fs.cidx[cpos] = index0(slot, ln) + b;
+          fs.cgtb[cpos] = (gt_base + g_before + __popc(gt_bits & below)) | ((uint32_t)(wv * kFastSlots + slot) << 24);
+        }
+      }
+    };
+    auto place_scalar = [&](int slot) {
+      const uint32_t w = fs.marks[slot][tid];
+      uint32_t total;
+      const uint32_t before = wave_exclusive_scan((w & 1u) | (w & 0x10000u), &total);
+      place_word(slot, lane, run_gt + (before & 0xffffu), run_c + (before >> 16));
+      run_gt += total & 0xffffu;
+      run_c += total >> 16;
+    };
+    if (has_lead) place_scalar(0);
+    if (n_tiles > 0) {
+      // The wavefront's n_tiles * 64 words form one sequence in index order (tile, lane).  Lane l takes
+      // the n_tiles consecutive words from n_tiles * l on, so that one wavefront scan serves all tiles.
+      uint32_t sum = 0;
+      for (int i = 0; i < n_tiles; ++i) {
+        const int f = n_tiles * lane + i;
+        const uint32_t w = fs.marks[1 + (f >> 6)][wv * 64 + (f & 63)];
+        sum += __popc(w & 0xffffu) | (__popc(w >> 16) << 16);
+      }
+      uint32_t total;
+      const uint32_t before = wave_exclusive_scan(sum, &total);
+      uint32_t g_run = run_gt + (before & 0xffffu), c_run = run_c + (before >> 16);
+      for (int i = 0; i < n_tiles; ++i) {
+        const int f = n_tiles * lane + i;
+        const uint32_t w = fs.marks[1 + (f >> 6)][wv * 64 + (f & 63)];
+        place_word(1 + (f >> 6), f & 63, g_run, c_run);
+        g_run += __popc(w & 0xffffu);
+        c_run += __popc(w >> 16);
+      }
+      run_gt += total & 0xffffu;
+      run_c += total >> 16;
+    }
+    if (has_tail) place_scalar(kFastSlots - 1);
+  }
+  __syncthreads();
+  const int nc = (int)min(c_all, (uint32_t)kCandCap);
+  for (int c = tid; c < nc; c += kSelThreads) fs.ckey[c] = ordered_key(x[fs.cidx[c]]);   // read again: cache hits
+
+  // ---- 3. the rest of the threshold: the r-th largest of the nc listed keys (digits of 11 and 10
+  // bits; the first 11 bits are the same for all of them)
+  const uint32_t r = min(take, (uint32_t)nc);
+  int buf = 0;
+  if (nc > 0) {
+    for (int b = tid; b < 2048; b += kSelThreads) fs.hist[b] = 0;
+    __syncthreads();
+    for (int c = tid; c < nc; c += kSelThreads) atomicAdd(&fs.hist[(fs.ckey[c] >> 10) & 2047u], 1u);
+    __syncthreads();
+    uint32_t total;
+    {
+      const int b0 = 2047 - 2 * tid, b1 = 2046 - 2 * tid;
+      const uint32_t c0 = fs.hist[b0], c1 = fs.hist[b1];
+      const uint32_t above = block_exclusive_scan(c0 + c1, fs.wave_tot[buf], &total);
+      buf ^= 1;
+      if (above < r && r <= above + c0) { fs.found[0] = (uint32_t)b0; fs.found[1] = r - above; }
+      else if (above + c0 < r && r <= above + c0 + c1) { fs.found[0] = (uint32_t)b1; fs.found[1] = r - above - c0; }
+    }
+    __syncthreads();
+    const uint32_t d1 = fs.found[0], r1 = fs.found[1];
+    fs.hist[tid] = 0;                           // 1024 bins, one per thread
+    __syncthreads();
+    for (int c = tid; c < nc; c += kSelThreads) {
+      const uint32_t k = fs.ckey[c];
+      if (((k >> 10) & 2047u) == d1) atomicAdd(&fs.hist[k & 1023u], 1u);
+    }
+    __syncthreads();
+    {
+      const int b0 = 1023 - tid;
+      const uint32_t c0 = fs.hist[b0];
+      const uint32_t above = block_exclusive_scan(c0, fs.wave_tot[buf], &total);
+      buf ^= 1;
+      if (above < r1 && r1 <= above + c0) { fs.found[0] = (uint32_t)b0; fs.found[1] = r1 - above; }
+    }
+    __syncthreads();
+    const uint32_t thr21 = (d1 << 10) | fs.found[0], need_eq = fs.found[1];
+
+    // selected candidates, in list (= index) order; their indices overwrite the keys (position <=
+    // list position, and every key of a round is read before the round's scan)
+    uint32_t run_sg = 0, run_eq = 0;
+    for (int c0 = 0; c0 < nc; c0 += kSelThreads) {
+      const int c = c0 + tid;
+      const uint32_t k21 = c < nc ? fs.ckey[c] & 0x1fffffu : 0u;
+      const bool is_gt = c < nc && k21 > thr21, is_eq = c < nc && k21 == thr21;
+      const uint32_t before = block_exclusive_scan((is_gt ? 1u : 0u) | (is_eq ? 1u << 16 : 0u), fs.wave_tot[buf], &total);
+      buf ^= 1;
+      const uint32_t eq_b = run_eq + (before >> 16);
+      if (is_gt || (is_eq && eq_b < need_eq)) {
+        const uint32_t pos = run_sg + (before & 0xffffu) + min(eq_b, need_eq);
+        const int32_t j = fs.cidx[c];
+        const uint32_t gr = fs.cgtb[c];
+        fs.ckey[pos] = (uint32_t)j;
+        out[(gr & 0xffffffu) + pos] = j;
+        atomicAdd(&fs.range_sel[gr >> 24], 1u);
+      }
+      run_sg += total & 0xffffu;
+      run_eq += total >> 16;
+    }
+  }
+  __syncthreads();
+  // counts per range -> selected candidates before each range (one wavefront, 4 ranges per lane)
+  static_assert(kFastRanges == 256, "four ranges per lane");
+  if (tid < 64) {
+    uint32_t v[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = fs.range_sel[4 * tid + i]; sum += v[i]; }
+    uint32_t all;
+    uint32_t run = wave_exclusive_scan(sum, &all);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { fs.range_sel[4 * tid + i] = run; run += v[i]; }
+    if (tid == 63) fs.range_sel[kFastRanges] = all;
+  }
+  __syncthreads();
+
+  // ---- 4. winners: position = winners before + selected candidates with a smaller index (those of
+  // earlier ranges, plus those of the wavefront's own range that precede the winner)
+  const int32_t *sidx = reinterpret_cast<const int32_t *>(fs.ckey);
+  auto emit_winners = [&](int slot) {
+    const uint32_t mk = fs.marks[slot][tid];
+    uint32_t bits = mk & 0xffffu;
+    if (bits == 0) return;
+    const int s0 = (int)fs.range_sel[wv * kFastSlots + slot], s1 = (int)fs.range_sel[wv * kFastSlots + slot + 1];
+    uint32_t pos = gt_base + (mk >> 16);
+    const int j0 = index0(slot, lane);
+    // selected candidates of the range before the thread's first winner: binary search; the
+    // thread's other winners follow within 16 indices, so the count is advanced one by one
+    int lo = s0, hi = s1;
+    const int first = j0 + (__ffs(bits) - 1);
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (sidx[mid] < first) lo = mid + 1; else hi = mid;
+    }
+    for (; bits != 0; bits &= bits - 1) {
+      const int j = j0 + (__ffs(bits) - 1);
+      while (lo < s1 && sidx[lo] < j) ++lo;
+      out[pos + (uint32_t)lo] = j;
+      ++pos;
+    }
+  };
+  if (has_lead) emit_winners(0);
+  for (int tile = 0; tile < n_tiles; ++tile) emit_winners(1 + tile);
+  if (has_tail) emit_winners(kFastSlots - 1);
+}
+
 // Writes the `count` (1 <= count <= m) indices of the largest x[0..m) to out, ascending,
-// equal values taken from the low-index end.
+// equal values taken from the low-index end.  lds: kSelLdsBytes of LDS.  first_digit, when not
+// null: the row's histogram of the first digit (2048 counters by ordered digit), already counted.
 __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int m, int count,
-                                               int32_t *__restrict__ out, SelShared &sh) {
+                                               int32_t *__restrict__ out, unsigned char *lds,
+                                               const uint32_t *__restrict__ first_digit = nullptr) {
+  SelShared &sh = *reinterpret_cast<SelShared *>(lds);
   const RowSplit rs = split_row(x, m);
-  uint32_t thr_key, need_eq;
-  radix_threshold(x, m, rs, count, sh, &thr_key, &need_eq);
-  emit_selected(x, m, rs, thr_key, need_eq, out, sh);
+  uint32_t prefix = 0, mask = 0, remaining = (uint32_t)count;
+  uint32_t in_bin;
+  if (first_digit != nullptr) {
+    const int tid = threadIdx.x;
+    in_bin = decide_from_counts(sh, 0, first_digit[2047 - 2 * tid], first_digit[2046 - 2 * tid], prefix, mask, remaining);
+  } else {
+    histogram_pass(x, m, rs, prefix, mask, 21, 2048, sh);
+    in_bin = decide_digit(sh, 0, prefix, mask, remaining);
+  }
+  if (rs.nv <= kFastMaxVec && in_bin <= (uint32_t)kCandCap) {
+    select_after_first_digit(x, m, rs, prefix >> 21, remaining, out, *reinterpret_cast<FastShared *>(lds));
+    return;
+  }
+  histogram_pass(x, m, rs, prefix, mask, 10, 2048, sh);
+  (void)decide_digit(sh, 1, prefix, mask, remaining);
+  histogram_pass(x, m, rs, prefix, mask, 0, 1024, sh);
+  (void)decide_digit(sh, 2, prefix, mask, remaining);
+  emit_selected(x, m, rs, prefix, remaining, out, sh);
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims d, SeqTab t,
                                                              const float *__restrict__ pooled,
-                                                             int32_t *__restrict__ idx) {
-  __shared__ SelShared sh;
+                                                             int32_t *__restrict__ idx,
+                                                             const uint32_t *__restrict__ hist0) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
   const int unit = blockIdx.x;
   const int g = unit % d.Hkv;
   const int s = (unit / d.Hkv) % d.S;
@@ -398,14 +751,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims d, SeqTab t,
   int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + (int64_t)g * n_keep;
   for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;   // window, last
   for (int x = count + d.w + threadIdx.x; x < n_keep; x += kSelThreads) out[x] = -1;   // unused slots
-  if (count > 0) select_top_row(row, m, count, out, sh);
+  if (count > 0) select_top_row(row, m, count, out, sel_lds, hist0 != nullptr ? hist0 + (int64_t)unit * 2048 : nullptr);
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_row_kernel(const float *__restrict__ row,
                                                                  int m, int count,
                                                                  int32_t *__restrict__ sel) {
-  __shared__ SelShared sh;
-  if (count > 0) select_top_row(row, m, count, sel, sh);
+  extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
+  if (count > 0) select_top_row(row, m, count, sel, sel_lds);
 }
 
 // ----------------------------------------------------------------------------------
@@ -679,7 +1032,7 @@ __global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab 
                                                                  const int32_t *__restrict__ head_off,
                                                                  const uint32_t *__restrict__ state,
                                                                  int32_t *__restrict__ idx) {
-  __shared__ SelShared sh;
+  extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
   const int unit = blockIdx.x;
   const int g = unit % d.Hkv;
   const int ls = unit / d.Hkv;
@@ -696,8 +1049,9 @@ __global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab 
   if (count <= 0) return;
   const uint32_t *st = state + (int64_t)ls * kAdaStateWords(d.Hkv);
   const uint32_t known = st[2 + 2 * d.Hkv + g];
-  if (known & 0x80000000u) emit_selected(row, m, split_row(row, m), st[0], known & 0x7fffffffu, out, sh);
-  else select_top_row(row, m, count, out, sh);
+  if (known & 0x80000000u)
+    emit_selected(row, m, split_row(row, m), st[0], known & 0x7fffffffu, out, *reinterpret_cast<SelShared *>(sel_lds));
+  else select_top_row(row, m, count, out, sel_lds);
 }
 
 // ----------------------------------------------------------------------------------
@@ -744,7 +1098,7 @@ __global__ __launch_bounds__(kSelThreads) void expand_kernel(
 }  // namespace
 
 hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
-                              hipStream_t st) {
+                              hipStream_t st, uint32_t *hist0) {
   const Dims &d = pl.d;
   int max_n = 0;
   for (int s = 0; s < d.S; ++s) max_n = max(max_n, pl.t.cu[s + 1] - pl.t.cu[s]);
@@ -758,7 +1112,7 @@ hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, f
   pm.outer_max = d.reduce_max && d.head_max;
   pm.plane_stride = (int64_t)d.L * d.Hkv * d.T;
   hipLaunchKernelGGL(reduce_pool_kernel, dim3((unsigned)blocks), dim3(kPoolThreads), 0, st, d, pl.t,
-                     pm, planes, raw, pooled, tiles);
+                     pm, planes, raw, pooled, tiles, hist0);
   return hipGetLastError();
 }
 
@@ -790,7 +1144,7 @@ hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_
 }
 
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, uint32_t *hist, uint32_t *state,
-                         hipStream_t st) {
+                         hipStream_t st, const uint32_t *hist0) {
   const Dims &d = pl.d;
   const int64_t rows = (int64_t)d.L * d.S * d.Hkv;
   if (pl.sel_parts > 1 && hist != nullptr && state != nullptr) {
@@ -804,7 +1158,9 @@ hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, uint
     hipLaunchKernelGGL(msel_emit_kernel, wide, block, 0, st, d, pl.t, pooled, P, pl.sel_part_len, state, idx);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), 0, st, d, pl.t, pooled, idx);
+  const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(select_kernel), kSelLdsBytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)rows), dim3(kSelThreads), kSelLdsBytes, st, d, pl.t, pooled, idx, hist0);
   return hipGetLastError();
 }
 
@@ -818,14 +1174,18 @@ hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *poole
     hipLaunchKernelGGL(ada_decide_kernel, dim3(pairs), dim3(kSelThreads), 0, st, d, pl.t, c_floor, level,
                        state, hist, head_off);
   }
-  hipLaunchKernelGGL(select_ada_kernel, dim3(pairs * d.Hkv), dim3(kSelThreads), 0, st, d, pl.t, pooled,
+  const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(select_ada_kernel), kSelLdsBytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_ada_kernel, dim3(pairs * d.Hkv), dim3(kSelThreads), kSelLdsBytes, st, d, pl.t, pooled,
                      head_off, state, idx);
   return hipGetLastError();
 }
 
 hipError_t launch_select_row(const float *pooled_row, int32_t m, int32_t count, int32_t *sel,
                              hipStream_t st) {
-  hipLaunchKernelGGL(select_row_kernel, dim3(1), dim3(kSelThreads), 0, st, pooled_row, m, count, sel);
+  const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(select_row_kernel), kSelLdsBytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_row_kernel, dim3(1), dim3(kSelThreads), kSelLdsBytes, st, pooled_row, m, count, sel);
   return hipGetLastError();
 }
 

@@ -60,6 +60,10 @@ struct Plan {
   // selection of long rows in calls with few rows: parts per row (1: not split), keys per part, scratch
   int32_t sel_parts, sel_part_len;
   size_t off_sel_hist, off_sel_state;
+  // first-digit histograms of the pooled rows (2048 counters per row), filled by the pooling kernel
+  // of a fused call so that selection starts at the second read; hist0_words == 0: not used
+  size_t off_hist0;
+  int64_t hist0_words;
 };
 
 inline __host__ __device__ int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -82,6 +86,10 @@ __device__ inline int live_tail0(const Dims &d, const SeqTab &t, int s, int n, i
   return visible / kt * kt;
 }
 
+// Raises a kernel's dynamic LDS limit; the runtime call is made once per (device, kernel, size)
+// and remembered (score.hip).
+hipError_t allow_dynamic_lds(const void *kernel, size_t bytes);
+
 // Kernel launchers (each returns the hipError of its launches).
 hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const int32_t *idx,
                           void *k_out, void *v_out, hipStream_t st);
@@ -89,9 +97,12 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const in
 // row statistics, before pass 2 and after pass 2.
 // `lse_in`, when not null, holds natural-log row normalisers [L][S][R][Hq]; the row-statistics
 // sweep is skipped and only the column reduction runs.
+// `clear`, when not null, is scratch of clear_words 32-bit words that the call leaves zeroed (done
+// by the small kernel between the sweeps: the fused calls need zeroed counters for the pooling
+// kernel and must not use a memset, which a captured graph may not contain).
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
                         float *planes, hipStream_t st, hipEvent_t *events = nullptr,
-                        const float *lse_in = nullptr);
+                        const float *lse_in = nullptr, uint32_t *clear = nullptr, int64_t clear_words = 0);
 // True when sweep `pass` (1 row statistics, 2 column reduction) over the unmasked chunks of this
 // plan runs in the Q-stationary kernel (score_qs.hip) rather than the tile-streaming one
 // (score.hip); diagnostics only.
@@ -111,8 +122,10 @@ __host__ __device__ inline bool decode_row(const Dims &d, const ScoreGeom &g, in
 }
 
 // out rows = (layer, seq, head): pooled/raw in the "scores" layout from RS planes.
+// hist0, when not null: [rows][2048] zeroed counters; the kernel adds the first-digit histogram of
+// every row's pooled scores (the non-window entries), for launch_select.
 hipError_t launch_reduce_pool(const Plan &pl, const float *planes, float *raw, float *pooled,
-                              hipStream_t st);
+                              hipStream_t st, uint32_t *hist0 = nullptr);
 // single output row summing every plane of a one-sequence call (prompt-token selection)
 hipError_t launch_reduce_pool_all(const Plan &pl, const float *planes, float *raw, float *pooled,
                                   hipStream_t st);
@@ -121,8 +134,9 @@ hipError_t launch_pool_row(const float *in, float *out, int32_t n_in, int32_t n_
                            hipStream_t st);
 // hist / state: scratch of the split-row path (off_sel_hist, off_sel_state); with either null, or when
 // the plan does not split rows (sel_parts == 1), every row is ranked by one workgroup.
+// hist0, when not null: the rows' first-digit histograms from launch_reduce_pool (one-workgroup path).
 hipError_t launch_select(const Plan &pl, const float *pooled, int32_t *idx, uint32_t *hist, uint32_t *state,
-                         hipStream_t st);
+                         hipStream_t st, const uint32_t *hist0 = nullptr);
 // Shared layer budget: head offsets from a layer-wide threshold, then per-head selection.
 // hist: L*S*Hkv*2048 uint32, state: L*S*(2 + 3*Hkv) uint32 of scratch.
 hipError_t launch_select_ada(const Plan &pl, int32_t c_floor, const float *pooled, int32_t *idx,

@@ -998,6 +998,42 @@ def test_select_on_a_three_million_key_row(S):
             assert np.array_equal(got[g], want[g]), (g, ws is None)
 
 
+@pytest.mark.parametrize("m,in_bin", [(20000, 4096), (20000, 4097), (20000, 40), (229376, 300), (229379, 300),
+                                      (229381, 300), (131072, 4000)])
+def test_select_around_the_limits_of_the_one_read_path(S, m, in_bin):
+    """The one-workgroup selection reads a row once more after the first radix digit when the row is
+    short enough (229376 entries plus up to three unaligned ones at either end) and the
+    threshold's first-digit bin holds at most 4096 entries; otherwise it runs all three digits.
+    Both sides of both limits, with runs of equal values and several budgets, against the oracle.
+    [1, 1.25) is one first-digit bin (sign, exponent and two mantissa bits)."""
+    n_window, H = 3, 3                        # odd row length: the rows start at different alignments
+    n = m + n_window
+    rng = np.random.default_rng(m + in_bin)
+    rows = np.empty((H, n), dtype=np.float32)
+    n_above = 700
+    for g in range(H):
+        r = (rng.random(n) * 0.5).astype(np.float32)                            # below the bin
+        pos = rng.permutation(m)[:in_bin + n_above]
+        r[pos[:in_bin]] = (1.0 + 0.25 * rng.random(in_bin)).astype(np.float32)   # the bin [1, 1.25)
+        r[pos[in_bin:]] = (2.0 + rng.random(n_above)).astype(np.float32)         # above it
+        if g == 1:                                                              # runs of equal values inside the bin
+            r[pos[:in_bin]] = np.float32(1.0) + np.float32(0.25 / 8) * rng.integers(0, 8, size=in_bin).astype(np.float32)
+        rows[g] = r
+    pooled = torch.from_numpy(rows.reshape(1, -1)).cuda()
+    for c_max in (n_above + 1, n_above + in_bin // 2, n_above + in_bin):         # threshold inside the bin
+        w = workloads.SpecKVWorkload(
+            name="limits", n_layers=1, n_q_heads=H, n_kv_heads=H, head_dim=64, seq_lens=(n,),
+            n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+        p = make_params(S, w)
+        idx = torch.full((1, H * S.total_keep(p)), -1, dtype=torch.int32, device="cuda")
+        S.speckv_select(p, pooled, idx)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy().reshape(H, -1)
+        for g in range(H):
+            want = orc.keep_indices(rows[g, :m].astype(np.float64), n, n_window, c_max)
+            assert np.array_equal(got[g], want), (c_max, g)
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_split_row_selection_ragged(S, seed):
     """Few long ragged rows (split over workgroups, parts past a short row's end are empty) with
