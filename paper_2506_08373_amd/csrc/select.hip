@@ -453,31 +453,32 @@ struct FastShared {
 };
 constexpr size_t kSelLdsBytes = sizeof(FastShared) > sizeof(SelShared) ? sizeof(FastShared) : sizeof(SelShared);
 
-// Smallest and largest float of first-digit bin `bin` (ordered digit).  Bins that hold NaN
-// patterns are cut at the infinities, and the bin just below zero ends at the largest negative
-// number (zero of either sign belongs to the bin above).
-__device__ __forceinline__ void bin_bounds(uint32_t bin, float *lo, float *hi) {
-  if (bin >= 1024u) {
-    const uint32_t base = (bin - 1024u) << 21;
-    *lo = __uint_as_float(min(base, 0x7f800000u));
-    *hi = __uint_as_float(min(base | 0x1fffffu, 0x7f800000u));
-  } else {
-    const uint32_t base = (2047u - bin) << 21;                  // sign bit set
-    *lo = __uint_as_float(min(base | 0x1fffffu, 0xff800000u));
-    *hi = __uint_as_float(min(max(base, 0x80000001u), 0xff800000u));
+// Smallest and largest float whose ordered key starts with the `bits` (11 or 22) leading bits of
+// `prefix`.  Ranges that hold NaN patterns are cut at the infinities, and a range that would end at
+// -0 ends at the largest negative number instead (zero of either sign has the key of +0).
+__device__ __forceinline__ void prefix_bounds(uint32_t prefix, int bits, float *lo, float *hi) {
+  const uint32_t low = 0xffffffffu >> bits;                     // the key bits the prefix leaves open
+  const uint32_t k_lo = prefix & ~low, k_hi = prefix | low;     // smallest / largest key of the range
+  if (prefix & 0x80000000u) {                                   // positive numbers: bits = key without the top bit
+    *lo = __uint_as_float(min(k_lo ^ 0x80000000u, 0x7f800000u));
+    *hi = __uint_as_float(min(k_hi ^ 0x80000000u, 0x7f800000u));
+  } else {                                                      // negative numbers: bits = ~key
+    *lo = __uint_as_float(min(~k_lo, 0xff800000u));
+    *hi = __uint_as_float(min(max(~k_hi, 0x80000001u), 0xff800000u));
   }
 }
 
-// The `take` largest entries of first-digit bin `bin` plus every entry of a higher bin, indices
-// ascending, ties to the lower index (see above).  rs.nv <= kFastMaxVec and at most kCandCap
-// entries in the bin.
-__device__ __forceinline__ void select_after_first_digit(const float *__restrict__ x, int m, RowSplit rs,
-                                                         uint32_t bin, uint32_t take,
-                                                         int32_t *__restrict__ out, FastShared &fs) {
+// The threshold's key starts with the `bits` (11: one digit decided, 22: two) leading bits of
+// `prefix`.  Writes the `take` largest of the entries whose key starts the same way plus every
+// larger entry, indices ascending, ties to the lower index (see above).  rs.nv <= kFastMaxVec and
+// at most kCandCap entries share the prefix.
+__device__ __forceinline__ void select_after_prefix(const float *__restrict__ x, int m, RowSplit rs,
+                                                    uint32_t prefix, int bits, uint32_t take,
+                                                    int32_t *__restrict__ out, FastShared &fs) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   float lo_f, hi_f;
-  bin_bounds(bin, &lo_f, &hi_f);
+  prefix_bounds(prefix, bits, &lo_f, &hi_f);
   // the wavefront's part of the vectors: whole tiles, the same number for every wavefront
   const int part_vec = ((rs.nv + kSelWaves - 1) / kSelWaves + kWaveTileVec - 1) / kWaveTileVec * kWaveTileVec;
   const int v_begin = min(wv * part_vec, rs.nv), v_end = min(v_begin + part_vec, rs.nv);
@@ -602,23 +603,26 @@ __device__ __forceinline__ void select_after_first_digit(const float *__restrict
   const int nc = (int)min(c_all, (uint32_t)kCandCap);
   for (int c = tid; c < nc; c += kSelThreads) fs.ckey[c] = ordered_key(x[fs.cidx[c]]);   // read again: cache hits
 
-  // ---- 3. the rest of the threshold: the r-th largest of the nc listed keys (digits of 11 and 10
-  // bits; the first 11 bits are the same for all of them)
+  // ---- 3. the rest of the threshold: the r-th largest of the nc listed keys, by the digits that
+  // are still open (11 and 10 bits, or the last 10 bits only)
   const uint32_t r = min(take, (uint32_t)nc);
   int buf = 0;
   if (nc > 0) {
-    for (int b = tid; b < 2048; b += kSelThreads) fs.hist[b] = 0;
-    __syncthreads();
-    for (int c = tid; c < nc; c += kSelThreads) atomicAdd(&fs.hist[(fs.ckey[c] >> 10) & 2047u], 1u);
-    __syncthreads();
     uint32_t total;
-    {
+    if (bits == 11) {
+      for (int b = tid; b < 2048; b += kSelThreads) fs.hist[b] = 0;
+      __syncthreads();
+      for (int c = tid; c < nc; c += kSelThreads) atomicAdd(&fs.hist[(fs.ckey[c] >> 10) & 2047u], 1u);
+      __syncthreads();
       const int b0 = 2047 - 2 * tid, b1 = 2046 - 2 * tid;
       const uint32_t c0 = fs.hist[b0], c1 = fs.hist[b1];
       const uint32_t above = block_exclusive_scan(c0 + c1, fs.wave_tot[buf], &total);
       buf ^= 1;
       if (above < r && r <= above + c0) { fs.found[0] = (uint32_t)b0; fs.found[1] = r - above; }
       else if (above + c0 < r && r <= above + c0 + c1) { fs.found[0] = (uint32_t)b1; fs.found[1] = r - above - c0; }
+    } else if (tid == 0) {
+      fs.found[0] = (prefix >> 10) & 2047u;     // the second digit is part of the prefix
+      fs.found[1] = r;
     }
     __syncthreads();
     const uint32_t d1 = fs.found[0], r1 = fs.found[1];
@@ -724,11 +728,15 @@ __device__ __forceinline__ void select_top_row(const float *__restrict__ x, int 
     in_bin = decide_digit(sh, 0, prefix, mask, remaining);
   }
   if (rs.nv <= kFastMaxVec && in_bin <= (uint32_t)kCandCap) {
-    select_after_first_digit(x, m, rs, prefix >> 21, remaining, out, *reinterpret_cast<FastShared *>(lds));
+    select_after_prefix(x, m, rs, prefix, 11, remaining, out, *reinterpret_cast<FastShared *>(lds));
     return;
   }
   histogram_pass(x, m, rs, prefix, mask, 10, 2048, sh);
-  (void)decide_digit(sh, 1, prefix, mask, remaining);
+  in_bin = decide_digit(sh, 1, prefix, mask, remaining);
+  if (rs.nv <= kFastMaxVec && in_bin <= (uint32_t)kCandCap) {
+    select_after_prefix(x, m, rs, prefix, 22, remaining, out, *reinterpret_cast<FastShared *>(lds));
+    return;
+  }
   histogram_pass(x, m, rs, prefix, mask, 0, 1024, sh);
   (void)decide_digit(sh, 2, prefix, mask, remaining);
   emit_selected(x, m, rs, prefix, remaining, out, sh);
