@@ -209,7 +209,8 @@ speckv_status speckv_compress(const speckv_params *p, const void *q, const void 
  * 256K tokens, or a few layers of shorter prompts).  Every call on a GPU shares that GPU's array:
  * calls that overlap on one GPU (two streams, two threads) race and must be serialised by the
  * caller.  The array keeps the previous call's contents; the kernels never read what they have
- * not written in the same call, so nothing needs clearing. */
+ * not written in the same call, and the counters that must start at zero are zeroed by a kernel of
+ * the same call (no memset). */
 #define SPECKV_STATIC_SCRATCH_BYTES (32u << 20)
 speckv_status speckv_compress_static(const speckv_params *p, const void *q, const void *k,
                                      const void *v, int32_t *idx, void *k_out, void *v_out,
