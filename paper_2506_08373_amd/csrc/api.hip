@@ -152,6 +152,22 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   if (kc_few > kChunkSmallCap) kc_few = kChunkSmallCap;
   if (kc < kc_few) kc = kc_few;
   if (kc < kChunkMin) kc = kChunkMin;
+  // The masked tails run as workgroups of the same launch (one per unit and sequence).  When the
+  // chunk workgroups alone fit one round of the CUs but not together with the tails, the chunk
+  // workgroups that have to wait for a tail's CU finish a tail's duration after all others;
+  // chunks up to a quarter longer that bring everything into one round are cheaper.
+  {
+    auto chunk_wgs = [&](int64_t kc_) {
+      int64_t chunks = 0;
+      for (int s = 0; s < d.S; ++s) chunks += (t.tail0[s] + kc_ - 1) / kc_;
+      return chunks * units;
+    };
+    const int64_t tails = units * d.S;
+    if (chunk_wgs(kc) <= kCUs && chunk_wgs(kc) + tails > kCUs) {
+      for (int64_t longer = kc + kt; longer <= kc + kc / 4; longer += kt)
+        if (chunk_wgs(longer) + tails <= kCUs) { kc = longer; break; }
+    }
+  }
   g.KC = (int32_t)kc;
   t.cc[0] = 0;
   for (int s = 0; s < d.S; ++s) t.cc[s + 1] = t.cc[s] + (t.tail0[s] + g.KC - 1) / g.KC;
