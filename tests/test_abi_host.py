@@ -200,6 +200,14 @@ def test_plan_of_the_benchmark_configurations(lib):
     assert c5["tile_keys"] == 256 and (c5["waves"], c5["blocks_per_wave"]) == (8, 1)
     tiny = plan(workloads.tiny_fp32())
     assert (tiny["waves"], tiny["blocks_per_wave"]) == (4, 1) and tiny["tile_keys"] == 128
+    # one layer of the 8B shape: the chunk workgroups and the 8 masked-tail workgroups of a sweep share
+    # one launch and fit one round of the 256 CUs together (chunks a little longer than 1/32 of the prompt)
+    for n_in in (32768, 131072):
+        one = plan(workloads.llama8b_layer(n_in=n_in, n_layers=1))
+        kc, kt = one["chunk_keys"], one["tile_keys"]
+        unmasked = (n_in - 64 + 1) // kt * kt                       # keys every observation row may see, whole tiles
+        assert kc % kt == 0 and one["n_chunks"] == -(-unmasked // kc)
+        assert one["n_chunks"] * 8 + 8 <= 256 < -(-unmasked // (kc - kt)) * 8 + 8      # one tile shorter would not fit
 
 
 def test_plan_invariants_over_random_shapes(lib):
@@ -226,7 +234,7 @@ def test_plan_invariants_over_random_shapes(lib):
         assert st == 0
         info = S.plan_info(p)
         tile, kc = info["tile_keys"], info["chunk_keys"]
-        assert kc % 256 == 0 and kc % tile == 0 and kc >= 512
+        assert kc % tile == 0 and kc >= 512
         rows_per_wg = info["waves"] * info["blocks_per_wave"] * 32
         rp = (w_ + a_ + 31) // 32 * 32
         assert info["row_super_blocks"] * rows_per_wg >= G * min(rp, rows_per_wg) or rp > rows_per_wg
