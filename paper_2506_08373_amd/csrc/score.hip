@@ -434,22 +434,18 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
 #undef SPECKV_LOAD_BFRAG
 #undef SPECKV_FLUSH_TILE
 
-// A kernel with TAIL_ONLY = false is a whole sweep in one launch: its first A.tail_blocks
-// workgroups run the sequences' masked tails (one per (unit, sequence); the count is padded to a
-// multiple of 8 so that the chunk workgroups behind them keep their XCD assignment), the others one
-// unmasked chunk each.  The tails come first because they are short: their CUs are free again long
-// before the chunk workgroups run out.  TAIL_ONLY = true is the tails alone (calls without a
-// complete chunk, and the tails behind a Q-stationary sweep).
+// A kernel with TAIL_ONLY = false is a whole sweep in one launch: its first A.chunk_blocks
+// workgroups run one unmasked chunk each, the ones behind them the sequences' masked tails (one per
+// (unit, sequence)).  A tail is a short latency chain; behind the chunks it fills the CUs that the
+// last round of chunk workgroups frees one by one (ragged batches: 1 % faster than tails in front,
+// equal-length grids: the same).  TAIL_ONLY = true is the tails alone (calls without a complete
+// chunk, and the tails behind a Q-stationary sweep).
 template <int DT, int D, int MB, int NW, int PASS, int RED, bool TAIL_ONLY>
 __device__ __forceinline__ void score_dispatch(const ScoreArgs &A) {
   const int bid = blockIdx.x;
-  if (TAIL_ONLY) {
-    score_body<DT, D, MB, NW, PASS, RED, true>(A, bid);
-  } else if (bid < A.tail_blocks) {
-    if (bid < A.d.L * A.d.Hkv * A.g.RS * A.d.S) score_body<DT, D, MB, NW, PASS, RED, true>(A, bid);
-  } else {
-    score_body<DT, D, MB, NW, PASS, RED, false>(A, bid - A.tail_blocks);
-  }
+  if (TAIL_ONLY) score_body<DT, D, MB, NW, PASS, RED, true>(A, bid);
+  else if (bid < A.chunk_blocks) score_body<DT, D, MB, NW, PASS, RED, false>(A, bid);
+  else score_body<DT, D, MB, NW, PASS, RED, true>(A, bid - A.chunk_blocks);
 }
 
 // The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
@@ -552,13 +548,13 @@ hipError_t launch_sweep(const ScoreArgs &A0, size_t lds, hipStream_t st) {
   const int64_t tails = (int64_t)A.d.L * A.d.Hkv * A.g.RS * A.d.S;
   if (tails > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 block(NW * 64);
-  A.tail_blocks = 0;
+  A.chunk_blocks = 0;
   if (A.g.n_fast_chunks > 0 && !qs_supported(A, PASS)) {
     const int64_t items = (int64_t)A.g.n_fast_chunks * A.d.L * A.d.Hkv;
-    A.tail_blocks = (int)((tails + 7) / 8 * 8);
-    const int64_t wgs = (items + 7) / 8 * 8 * A.g.RS + A.tail_blocks;
-    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs);
+    const int64_t chunk_wgs = (items + 7) / 8 * 8 * A.g.RS;
+    if (chunk_wgs + tails > 0x7fffffffLL) return hipErrorInvalidValue;
+    A.chunk_blocks = (int)chunk_wgs;
+    const dim3 grid((unsigned)(chunk_wgs + tails));
     if (PASS == 1 && NW == 8) return launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
     return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
   }
@@ -624,7 +620,7 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
 bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
-  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.tail_blocks = 0; A.clear = nullptr; A.clear_words = 0;
+  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.chunk_blocks = 0; A.clear = nullptr; A.clear_words = 0;
   return qs_supported(A, pass);
 }
 
@@ -634,7 +630,7 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
   A.q = (const char *)q; A.k = (const char *)k;
-  A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in; A.tail_blocks = 0;
+  A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in; A.chunk_blocks = 0;
   A.clear = clear; A.clear_words = clear != nullptr ? clear_words : 0;
   switch (pl.d.dt) {
     case SPECKV_BF16: return pl.d.D == 128 ? dispatch_geom<kBf16, 128>(A, st, events) : dispatch_geom<kBf16, 64>(A, st, events);

@@ -20,7 +20,7 @@ struct ScoreArgs {
   float *planes;    // [RS][layer][Hkv*T]
   uint32_t *clear;  // optional scratch the kernel between the sweeps zeroes (clear_words words)
   int64_t clear_words;
-  int tail_blocks;  // whole-sweep launches: leading workgroups that run the masked tails (multiple of 8)
+  int chunk_blocks; // whole-sweep launches: workgroups that run unmasked chunks; the masked tails follow them
 };
 
 namespace {
