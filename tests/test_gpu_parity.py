@@ -998,6 +998,59 @@ def test_select_on_a_three_million_key_row(S):
             assert np.array_equal(got[g], want[g]), (g, ws is None)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_select_random_rows_distributions_and_budgets(S, seed):
+    """Selection on given scores over random row lengths (1 to 300 000 and the tile boundaries of the
+    kernel), value distributions (smooth, heavy-tailed, few levels, constant, runs of equal values as
+    max pooling leaves them, signed zeros and denormals), row alignments and budgets from 0 to beyond
+    the row: every row equal to the oracle's."""
+    rng = np.random.default_rng(7000 + seed)
+    for case in range(40):
+        H = int(rng.choice([1, 2, 3, 5]))
+        n_window = int(rng.choice([0, 1, 2, 3, 5, 64]))
+        kind = rng.choice(["tiny", "small", "mid", "big", "edge"])
+        m = {"tiny": lambda: rng.integers(1, 40), "small": lambda: rng.integers(40, 5000),
+             "mid": lambda: rng.integers(5000, 70000), "big": lambda: rng.integers(70000, 300000),
+             "edge": lambda: rng.choice([1023, 1024, 1025, 16383, 16384, 16385, 65536, 65537, 229375, 229376,
+                                         229377, 229380])}[kind]()
+        m = int(m)
+        n = m + n_window
+        dist = rng.choice(["normal", "lognormal", "levels", "const", "softmaxlike", "runs", "zeros"])
+        rows = np.zeros((H, n), dtype=np.float32)
+        for g in range(H):
+            if dist == "normal":
+                r = rng.standard_normal(n)
+            elif dist == "lognormal":
+                r = np.exp(3 * rng.standard_normal(n))
+            elif dist == "levels":
+                r = rng.integers(0, int(rng.choice([2, 5, 100, 5000])), size=n) / 7.0
+            elif dist == "const":
+                r = np.full(n, rng.choice([0.0, 1.5, -2.0]))
+            elif dist == "softmaxlike":
+                z = rng.standard_normal(n) * rng.choice([0.2, 1.0, 4.0])
+                r = np.exp(z - z.max())
+                r /= r.sum()
+            elif dist == "runs":
+                r = np.repeat(rng.random((n + 6) // 7), 7)[:n]
+            else:
+                r = rng.choice([0.0, -0.0, 1e-40, -1e-40, 1e-3, -1e-3], size=n)
+            rows[g] = r.astype(np.float32)
+        c_max = int(rng.choice([0, 1, 2, 17, 128, 1024, 2048, 5000, m // 2 + 1, max(m - 1, 0), m, m + 5]))
+        if n_window == 0 and c_max == 0:
+            c_max = 1                                    # nothing to keep is not a call
+        w = workloads.SpecKVWorkload(
+            name="random_rows", n_layers=1, n_q_heads=H, n_kv_heads=H, head_dim=64, seq_lens=(n,),
+            n_window=n_window, n_lookahead=1, pool_k=7, c_max=c_max, dtype="bf16", sm_scale=1.0)
+        p = make_params(S, w)
+        idx = torch.full((1, H * S.total_keep(p)), -7, dtype=torch.int32, device="cuda")
+        S.speckv_select(p, torch.from_numpy(rows.reshape(1, -1)).cuda(), idx)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy().reshape(H, -1)
+        for g in range(H):
+            want = orc.keep_indices(rows[g, :m].astype(np.float64), n, n_window, c_max)
+            assert np.array_equal(got[g], want), (seed, case, g, m, n_window, str(dist), c_max)
+
+
 @pytest.mark.parametrize("m,in_bin", [(20000, 4096), (20000, 4097), (20000, 40), (229376, 300), (229379, 300),
                                       (229381, 300), (131072, 4000)])
 def test_select_around_the_limits_of_the_one_read_path(S, m, in_bin):
