@@ -414,17 +414,19 @@ __device__ __forceinline__ void emit_selected(const float *__restrict__ x, int m
   }
 }
 
-// ---- rows of up to kFastMaxVec vectors: one more read after the first digit ----
-// Once the first digit is decided the threshold's bin is known.  Entries in higher bins are
-// selected whatever the other digits turn out to be ("winners"); only the entries of that bin
-// ("candidates", usually a small fraction of the row) decide the rest of the threshold.  So the
-// row is read just once more:
-//   1. every wavefront classifies a contiguous part of the row, tile by tile, and leaves per thread
-//      and tile a word of winner and candidate bits in LDS - no scans, no barriers;
+// ---- rows of up to kFastMaxVec vectors: one more read once a digit or two are decided ----
+// With the leading digit(s) of the threshold decided, the keys that start the same way form one
+// range of floats.  Entries above it are selected whatever the other digits turn out to be
+// ("winners"); only the entries inside it ("candidates", usually a small fraction of the row) decide
+// the rest of the threshold.  So the row is read just once more:
+//   1. every wavefront classifies a contiguous part of the row, tile by tile (two float compares
+//      per entry), and leaves per thread and tile a word of winner and candidate bits in LDS - no
+//      scans, no barriers;
 //   2. after one exchange of the wavefronts' totals each wavefront walks its words again (LDS only),
-//      turns the bit counts into positions with wavefront scans and appends its candidates to an
-//      LDS list in index order (ordered key, index, winners before);
-//   3. the remaining 21 bits of the threshold are found on that list;
+//      turns the bit counts into positions with one wavefront scan and appends its candidates to an
+//      LDS list in index order (index, winners before); the candidates' keys are then gathered by
+//      all threads together (the row is in cache);
+//   3. the remaining digits of the threshold are found on that list;
 //   4. every output position follows from counts that are already there:
 //        a selected candidate goes to  (winners before it) + (selected candidates before it),
 //        a winner to                   (winners before it) + (selected candidates with a smaller index).
