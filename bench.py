@@ -274,6 +274,13 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     mean_ms = _stage_means(hip, ev_sets, NE)
+    # Context figure: the same K steps without the stage events (seven event records between dependent
+    # kernels cost about 25 us per step: nothing on the 32-layer workload, a fifth of the tiny ones).
+    t0 = time.perf_counter()
+    for step in range(args.steps):
+        plain_call()
+    torch.cuda.synchronize()
+    plain_elapsed = time.perf_counter() - t0
 
     # algorithmic work per launch
     n_scores = float(w.n_rows) * w.n_q_heads * w.total_tokens * L          # score elements of one sweep
@@ -408,6 +415,8 @@ def main() -> int:
         "config": config,
         "roofline": roofline,
         "kernels": kernels,
+        "without_stage_events": {"ms_per_step": round(plain_elapsed / args.steps * 1e3, 4),
+                                 "value": round(w.key_units / (plain_elapsed / args.steps), 1), "unit": "keys/s"},
         "single_sweep_variant": lse_variant,
         "cpu_baseline": cpu_baseline,
         "parity_check": parity,
