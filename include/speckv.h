@@ -125,9 +125,11 @@ typedef struct {
                           m' = n' - n_window: scores at j >= n' are written as 0, idx holds
                           min(c_max, m') candidates, the window m'..n'-1 and then -1 up to the
                           host-sized row; compaction writes zero rows for the -1 entries.
-                          Supported by speckv_score(_lse), speckv_select, speckv_compact and
-                          speckv_compress(_lse, _events, _static); other entry points return
-                          SPECKV_ERR_UNSUPPORTED. */
+                          With per-head budgets head_off[Hkv] = Hkv * (min(c_max, m') + n_window)
+                          and the rows behind it hold -1 / zeros.
+                          Supported by speckv_score(_lse), speckv_select(_ada), speckv_compact(_ada)
+                          and speckv_compress(_lse, _events, _static, _ada); the prompt-token entry
+                          points (specpc_*) return SPECKV_ERR_UNSUPPORTED. */
 } speckv_params;
 
 /* Human-readable name of a status code (static storage). */

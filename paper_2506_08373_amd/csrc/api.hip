@@ -447,7 +447,6 @@ static speckv_status ada_plan(const speckv_params *p, int32_t c_floor, Plan *pl)
   speckv_status st = build_plan(p, pl, false, 0);
   if (st != SPECKV_OK) return st;
   if (c_floor < 0) return SPECKV_ERR_INVALID_ARG;
-  if (pl->d.n_dev != nullptr) return SPECKV_ERR_UNSUPPORTED;    // shared budgets take host-side lengths only
   if (pl->d.Hkv > SPECKV_MAX_ADA_HEADS) return SPECKV_ERR_UNSUPPORTED;
   return SPECKV_OK;
 }

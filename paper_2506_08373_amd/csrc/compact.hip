@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void compact_ada_kernel(
   const int s = ls % d.S;
   const int layer = ls / d.S;
   const int rows = d.Hkv * (t.ck[s + 1] - t.ck[s]);
-  const int n_s = t.cu[s + 1] - t.cu[s];
+  const int n_s = live_len(d, t, s);
   const int r = blk * (kThreads >> lpr_shift) + (threadIdx.x >> lpr_shift);
   if (r >= rows) return;
   // head of row r: the last g with head_off[g] <= r

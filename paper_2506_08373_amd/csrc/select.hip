@@ -922,8 +922,8 @@ __global__ __launch_bounds__(kSelThreads) void ada_hist_kernel(Dims d, SeqTab t,
   const int ls = unit / d.Hkv;
   const int s = ls % d.S;
   const int layer = ls / d.S;
-  const int n_s = t.cu[s + 1] - t.cu[s];
-  const int m = n_s - d.w;
+  const int n_s = t.cu[s + 1] - t.cu[s];                  // row stride
+  const int m = live_len(d, t, s) - d.w;
   const float *x = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
   const int shift = ada_shift(level), nb = ada_bins(level);
   const uint32_t mask = level == 0 ? 0u : level == 1 ? 0xffe00000u : 0xfffffc00u;
@@ -951,7 +951,7 @@ __global__ __launch_bounds__(kSelThreads) void ada_decide_kernel(Dims d, SeqTab 
   const int ls = blockIdx.x;
   const int s = ls % d.S;
   const int H = d.Hkv;
-  const int m = t.cu[s + 1] - t.cu[s] - d.w;
+  const int m = live_len(d, t, s) - d.w;
   const int C = min(d.c_max, m);
   const int f = min(c_floor, C);
   const unsigned long long need = (unsigned long long)H * (unsigned)(C - f);
@@ -1048,14 +1048,18 @@ __global__ __launch_bounds__(kSelThreads) void select_ada_kernel(Dims d, SeqTab 
   const int ls = unit / d.Hkv;
   const int s = ls % d.S;
   const int layer = ls / d.S;
-  const int n_s = t.cu[s + 1] - t.cu[s];
-  const int m = n_s - d.w;
+  const int n_s = t.cu[s + 1] - t.cu[s];                  // row stride
+  const int m = live_len(d, t, s) - d.w;
   const int32_t *ho = head_off + (int64_t)ls * (d.Hkv + 1);
   const int start = ho[g];
   const int count = min(max(ho[g + 1] - start - d.w, 0), m);
   const float *row = pooled + (int64_t)layer * d.Hkv * d.T + (int64_t)d.Hkv * t.cu[s] + (int64_t)g * n_s;
   int32_t *out = idx + (int64_t)layer * d.Hkv * d.KT + (int64_t)d.Hkv * t.ck[s] + start;
   for (int x = threadIdx.x; x < d.w; x += kSelThreads) out[count + x] = m + x;
+  if (g == d.Hkv - 1) {     // a live prompt shorter than the host's bound leaves slots behind the last head unused
+    const int used = ho[d.Hkv], slots = d.Hkv * (t.ck[s + 1] - t.ck[s]);
+    for (int x = used + threadIdx.x; x < slots; x += kSelThreads) out[x - start] = -1;
+  }
   if (count <= 0) return;
   const uint32_t *st = state + (int64_t)ls * kAdaStateWords(d.Hkv);
   const uint32_t known = st[2 + 2 * d.Hkv + g];

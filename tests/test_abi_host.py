@@ -112,7 +112,6 @@ def test_device_side_count_needs_one_sequence_and_supported_entry_points(lib):
     p.c.n_in_dev = 1026
     assert lib.speckv_compress(p.ref(), 256, 256, 256, 256, 256, 256, 256, 1 << 40, None) == -1
     p.c.n_in_dev = 1024
-    assert lib.speckv_select_ada(p.ref(), 0, 256, 256, 256, 256, 1 << 40, None) == -2
     assert lib.specpc_select_tokens(p.ref(), 10, 1, 256, 256, 256, 256, 256, 256, 256, 1 << 40, None) == -2
 
 

@@ -834,6 +834,43 @@ def test_device_side_token_count_equals_a_host_length_call(S, n_live, shape):
     assert bool((kd[..., keep_live:, :] == 0).all()) and bool((vd[..., keep_live:, :] == 0).all())
 
 
+@pytest.mark.parametrize("n_live", [6000, 3000, 700, 130])
+def test_shared_budget_with_device_side_token_count(S, n_live):
+    """Per-head budgets with `n_in_dev`: head offsets, indices and the compacted cache equal those of
+    a call whose host length is the live length; the slots a shorter prompt leaves behind the last
+    head hold -1 / zero rows."""
+    n_cap, c_floor = 7000, 100
+    w = workloads.llama8b_layer(n_in=n_cap, c_max=512, n_layers=2, name="devlen_ada")
+    t = workloads.generate(w)
+    q, k, v = (t[x].cuda() for x in ("q", "k", "v"))
+    n_dev = torch.tensor([n_live], dtype=torch.int32, device="cuda")
+    p_dev = S.SpecKVParams.for_tensors(q, k, seq_lens=(n_cap,), n_window=w.n_window, pool_k=w.pool_k,
+                                       c_max=w.c_max, sm_scale=w.sm_scale, n_in_dev=n_dev)
+    k_live, v_live = k[:, :n_live].contiguous(), v[:, :n_live].contiguous()
+    p_host = S.SpecKVParams.for_tensors(q, k_live, seq_lens=(n_live,), n_window=w.n_window, pool_k=w.pool_k,
+                                        c_max=w.c_max, sm_scale=w.sm_scale)
+    L, H, d = w.n_layers, w.n_kv_heads, w.head_dim
+    outs = {}
+    for name, p, kk, vv in (("dev", p_dev, k, v), ("host", p_host, k_live, v_live)):
+        KT = S.total_keep(p)
+        idx = torch.full((L, H * KT), -7, dtype=torch.int32, device="cuda")
+        head_off = torch.full((L, 1, H + 1), -7, dtype=torch.int32, device="cuda")
+        k_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
+        v_out = torch.full((L, H * KT, d), 3.0, dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(S.ada_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        S.speckv_compress_ada(p, c_floor, q, kk, vv, idx, head_off, k_out, v_out, ws)
+        torch.cuda.synchronize()
+        outs[name] = (idx, head_off, k_out, v_out)
+    idd, hod, kd, vd = outs["dev"]
+    idh, hoh, kh, vh = outs["host"]
+    assert torch.equal(hod, hoh)
+    used = idh.shape[1]                                   # H * (min(c_max, m_live) + n_window)
+    assert int(hoh[0, 0, H]) == used
+    assert torch.equal(idd[:, :used], idh) and bool((idd[:, used:] == -1).all())
+    assert torch.equal(kd[:, :used], kh) and torch.equal(vd[:, :used], vh)
+    assert bool((kd[:, used:] == 0).all()) and bool((vd[:, used:] == 0).all())
+
+
 def test_cascade_on_the_device_in_one_graph(S):
     """SpecKV-PC (Sec. "SpecKV-PC: Cascaded Compression") without a host round trip: the prompt-token
     selection leaves its data-dependent count on the device, the gather that stands in for the
