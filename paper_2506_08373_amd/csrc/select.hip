@@ -54,6 +54,24 @@ __device__ inline void reduce_pool_tile(const float *__restrict__ in, PlaneMerge
   // position further back than ahead, the library convention with padding k / 2)
   const int half = pool_k / 2, after = (pool_k - 1) / 2;
   const int span = kPoolTile + 2 * half;
+  constexpr int kPerThread = (kPoolTile + SPECKV_MAX_POOL_K + kPoolThreads - 1) / kPoolThreads;
+  if (pm.n_inner == 1 && pm.n_outer <= 2) {
+    // one or two planes (the usual case): every load of the thread is issued before the first is used
+    float r0[kPerThread], r1[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+      const int x = threadIdx.x + u * kPoolThreads, jj = j0 - half + x;
+      const bool ok = x < span && jj >= 0 && jj < n_s;
+      r0[u] = ok ? in[jj] : 0.f;
+      r1[u] = ok && pm.n_outer == 2 ? in[jj + pm.plane_stride] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) {
+      const int x = threadIdx.x + u * kPoolThreads;
+      const float a0 = pm.inner_max ? fmaxf(0.f, r0[u]) : r0[u], a1 = pm.inner_max ? fmaxf(0.f, r1[u]) : r1[u];
+      if (x < span) tile[x] = pm.outer_max ? fmaxf(fmaxf(0.f, a0), a1) : 0.f + a0 + a1;
+    }
+  } else
   for (int x = threadIdx.x; x < span; x += kPoolThreads) {
     const int jj = j0 - half + x;
     float acc = 0.f;
