@@ -322,6 +322,10 @@ def main() -> int:
 
     ms_per_step = elapsed / args.steps * 1e3
     value = w.key_units / (elapsed / args.steps)
+    # the same algorithmic flops (one Q.K^T; the two sweeps execute it twice) over the whole step
+    step_tflops = qk_flops / (ms_per_step * 1e-3) / 1e12
+    roofline["whole_step"] = {"achieved": round(step_tflops, 2), "unit": "TFLOP/s", "frac": round(step_tflops / peak_mfma, 4),
+                              "note": "algorithmic flops of one Q.K^T over the step time; each sweep executes them once"}
 
     # Context figure (not the headline): the same step when the caller already holds the row
     # log-sum-exps (e.g. from the prefill attention kernel) and scoring needs one sweep only.
