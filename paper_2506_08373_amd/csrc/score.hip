@@ -309,29 +309,29 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
               mrun[rb] = mnew;
             }
           } else {
-            // probabilities in batches of 8: all multiply-adds, then all exp2, then the reduction,
-            // so that no instruction waits on the transcendental issued just before it
+            // the 16 probabilities of a row block: all multiply-adds, then all exp2, then the reduction
+            // as a tree, so that no instruction waits on the one issued just before it (against
+            // two batches of 8 with a serial sum: the column sweep 2.4 % faster, the step 0.8 %)
             float colsum = 0.f;
 #pragma unroll
             for (int rb = 0; rb < NACT; ++rb) {
               if (RED == 1) colsum = 0.f;
+              float x[16];
 #pragma unroll
-              for (int h8 = 0; h8 < 16; h8 += 8) {
-                float x[8];
+              for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[rb][i], c2, nlse[rb][i]);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = fmaf(acc[rb][h8 + i], c2, nlse[rb][h8 + i]);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (RED == 0) {
-#pragma unroll
-                  for (int i = 0; i < 8; ++i) colsum += x[i];
-                } else {
-#pragma unroll
-                  for (int i = 0; i < 8; i += 2) colsum = fmaxf(fmaxf(colsum, x[i]), x[i + 1]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+              for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
+              __builtin_amdgcn_sched_barrier(0);
+              if (RED == 0) {
+                colsum += (((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]))) +
+                          (((x[8] + x[9]) + (x[10] + x[11])) + ((x[12] + x[13]) + (x[14] + x[15])));
+              } else {
+                const float t0 = fmaxf(fmaxf(x[0], x[1]), x[2]), t1 = fmaxf(fmaxf(x[3], x[4]), x[5]);
+                const float t2 = fmaxf(fmaxf(x[6], x[7]), x[8]), t3 = fmaxf(fmaxf(x[9], x[10]), x[11]);
+                const float t4 = fmaxf(fmaxf(x[12], x[13]), x[14]);
+                colsum = fmaxf(fmaxf(colsum, fmaxf(fmaxf(t0, t1), t2)), fmaxf(fmaxf(t3, t4), x[15]));
               }
+              __builtin_amdgcn_sched_barrier(0);
               if (RED == 1) {        // one value per 32-row block: blocks of a head are merged at the flush
                 colsum = max_other_half(colsum);
                 if (half == 0) csum[(size_t)buf * NW * MB * KT + (rb * NW + wv) * KT + kb * 32 + l32] = colsum;
