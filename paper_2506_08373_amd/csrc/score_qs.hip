@@ -228,9 +228,15 @@ __global__ __launch_bounds__(kQsWaves * 64) void score_qs_kernel(ScoreArgs A) {
       const float nref = -sx;
       float sum = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
+      for (int kb = 0; kb < KB; ++kb) {                    // per key block: multiply-adds, exp2, a tree of adds
+        float x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[kb][i], c2, nref));
+        for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[kb][i], c2, nref);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
+        sum += (((x[0] + x[1]) + (x[2] + x[3])) + ((x[4] + x[5]) + (x[6] + x[7]))) +
+               (((x[8] + x[9]) + (x[10] + x[11])) + ((x[12] + x[13]) + (x[14] + x[15])));
+      }
       sum = add_other_half(sum);                           // the row's keys of both lane halves
       float ref = sx, l = sy + sum;
       if (__builtin_amdgcn_ballot_w64(!(sum < kQsOverflow)) != 0) {
