@@ -12,7 +12,11 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspeckv.so")
-SOURCES = ["api.hip", "score.hip", "score_qs.hip", "select.hip", "compact.hip", "probe.hip"]
+SOURCES = ["api.hip", "score.hip", "score_rows.hip", "score_cols.hip", "score_qs.hip", "select.hip", "compact.hip",
+           "probe.hip"]
+# The column-reduction sweep is scheduled with the compiler's iterative-ILP strategy (5 % faster);
+# the same strategy costs the row-statistics sweep 3 %, so that one keeps the default.
+EXTRA_FLAGS = {"score_cols.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]}
 
 # Packed fp32 VALU ops are disabled on purpose; the host pass warns that it does not
 # know the feature, which is harmless.
@@ -36,7 +40,7 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-8000:]))

@@ -94,6 +94,9 @@ struct Tile {
 // rows stationary in LDS and each wave streaming its own keys through registers (score_qs.hip).
 // Returns false when the geometry is outside what that kernel is built for; then nothing was
 // launched and the caller uses the tile-streaming kernel.
+// The two sweeps over all chunks and masked tails of a call (score_rows.hip, score_cols.hip).
+hipError_t launch_row_statistics_sweep(const ScoreArgs &A, hipStream_t st);
+hipError_t launch_column_sweep(const ScoreArgs &A, hipStream_t st);
 bool qs_supported(const ScoreArgs &A, int pass);
 hipError_t launch_qs_sweep(const ScoreArgs &A, int pass, hipStream_t st);
 
