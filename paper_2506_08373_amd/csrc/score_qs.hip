@@ -1,6 +1,6 @@
 // Scoring sweeps with the query rows stationary in LDS (Sec. 3.1 Eq. 1; Alg. 1 CrossAttention
 // and reduce steps; App. C.2 for the GQA group).  An alternative to the tile-streaming kernel of
-// score.hip for the unmasked chunks of large groups: by default it runs the row-statistics sweep at
+// score_sweep.h for the unmasked chunks of large groups: by default it runs the row-statistics sweep at
 // d = 64; SPECKV_SCORE_KERNEL=qs selects it for every sweep it supports.
 //
 // Same mathematics (pass 1: per-row (reference, sum of exp2) over a chunk of keys; pass 2:
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kQsWaves * 64) void score_qs_kernel(ScoreArgs A) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // (layer, head, chunk, row super-block) of this workgroup: the RS super-blocks that sweep the
-  // same keys get linear ids 8 apart, i.e. the same XCD and its L2 (see score.hip)
+  // same keys get linear ids 8 apart, i.e. the same XCD and its L2 (see score_sweep.h)
   const int per_group = 8 * A.g.RS;
   const int grp = blockIdx.x / per_group, within = blockIdx.x % per_group;
   const int item = grp * 8 + (within & 7);

@@ -105,7 +105,7 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
                         const float *lse_in = nullptr, uint32_t *clear = nullptr, int64_t clear_words = 0);
 // True when sweep `pass` (1 row statistics, 2 column reduction) over the unmasked chunks of this
 // plan runs in the Q-stationary kernel (score_qs.hip) rather than the tile-streaming one
-// (score.hip); diagnostics only.
+// (score_sweep.h); diagnostics only.
 bool score_uses_qs(const Plan &pl, int pass);
 // Row `lr` of super-block `rs` -> (head in group, observation row); false for padding rows.
 // Heads never share a 32-row block: each head's R rows are padded to Rp, and a super-block holds
