@@ -113,6 +113,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   if (A.g.PPH == 1) nblk = min(A.g.HPS, d.G - rs * A.g.HPS) * (A.g.Rp / 32);
   else nblk = (min(RSB, d.R - (rs % A.g.PPH) * RSB) + 31) / 32;
   const int nact = __builtin_amdgcn_readfirstlane(max(0, min(MB, (nblk - wv + NW - 1) / NW)));
+  // Maximum over the query rows, full super-block, an even number of blocks per head: the wave
+  // takes two neighbouring blocks (2 wv and 2 wv + 1, the same head) instead, merges their
+  // column maxima in registers and hands one value per key to the flush, not two.  A maximum
+  // does not depend on the order, so the result is the same bit for bit.
+  const int blocks_per_head = (A.g.PPH == 1 ? A.g.Rp : RSB) / 32;
+  const bool paired = PASS == 2 && RED == 1 && !MASKED && MB == 2 && nblk == NW * MB && blocks_per_head % 2 == 0;
+  auto block_of = [&](int rb) { return paired ? wv * MB + rb : rb * NW + wv; };
   if (PASS == 2)   // slots of skipped blocks must read as zero when the tile partials are merged
     for (int x = tid; x < 2 * NW * MB * KT; x += NW * 64) csum[x] = 0.f;
 
@@ -122,7 +129,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
 #pragma unroll
   for (int rb = 0; rb < MB; ++rb) {
     int hh, i0;
-    const bool ok = decode_row(d, A.g, rs, (rb * NW + wv) * 32, &hh, &i0);
+    const bool ok = decode_row(d, A.g, rs, block_of(rb) * 32, &hh, &i0);
     blk_head[rb] = ok ? hh : -1;       // -1: the whole block is padding
     blk_i0[rb] = i0;
   }
@@ -190,7 +197,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int r32 = 8 * (i >> 2) + 4 * half + (i & 3);
-        const int lr = (rb * NW + wv) * 32 + r32;
+        const int lr = block_of(rb) * 32 + r32;
         const bool valid = SPECKV_ROW_VALID(rb, r32);
         const int io = blk_i0[rb] + r32;
         float v = -lp[rs * RSB + lr];                       // the lse buffer covers the padded rows
@@ -231,8 +238,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   float *plane_out = nullptr;
   if (PASS == 2)
     plane_out = A.planes + ((int64_t)rs * d.L + layer) * d.Hkv * d.T + (int64_t)d.Hkv * A.t.cu[s] + (int64_t)g * n_host;
-  const int blocks_per_head = (A.g.PPH == 1 ? A.g.Rp : RSB) / 32;
   const bool head_max = d.head_max != 0;
+  const int slots_per_head = paired ? blocks_per_head / 2 : blocks_per_head;
 #define SPECKV_FLUSH_TILE(tile_)                                                             \
   if (tid < KT) {                                                                            \
     const int key_ = key_begin + (tile_) * KT + tid;                                         \
@@ -242,14 +249,18 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
       if (RED == 0) {                                                                        \
         _Pragma("unroll") for (int w2 = 0; w2 < NW; ++w2) total_ += cp_[w2 * KT];            \
       } else {                                                                               \
-        /* per 32-row block maxima: max within a head, then heads added (or maxed) */        \
+        /* per block (or block pair) maxima: max within a head, then heads added (or maxed) */ \
         float cur_ = 0.f;                                                                    \
+        int in_head_ = 0;                                                                    \
         _Pragma("unroll") for (int b2 = 0; b2 < NW * MB; ++b2) {                             \
-          if (b2 > 0 && b2 % blocks_per_head == 0) {                                         \
+          if (paired && b2 >= NW) break;                                                     \
+          if (in_head_ == slots_per_head) {                                                  \
             total_ = head_max ? fmaxf(total_, cur_) : total_ + cur_;                         \
             cur_ = 0.f;                                                                      \
+            in_head_ = 0;                                                                    \
           }                                                                                  \
           cur_ = fmaxf(cur_, cp_[b2 * KT]);                                                  \
+          ++in_head_;                                                                        \
         }                                                                                    \
         total_ = head_max ? fmaxf(total_, cur_) : total_ + cur_;                             \
       }                                                                                      \
@@ -319,7 +330,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
             float colsum = 0.f;
 #pragma unroll
             for (int rb = 0; rb < NACT; ++rb) {
-              if (RED == 1) colsum = 0.f;
+              if (RED == 1 && !(paired && rb > 0)) colsum = 0.f;
               float x[16];
 #pragma unroll
               for (int i = 0; i < 16; ++i) x[i] = fmaf(acc[rb][i], c2, nlse[rb][i]);
@@ -336,13 +347,16 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
                 colsum = fmaxf(fmaxf(colsum, fmaxf(fmaxf(t0, t1), t2)), fmaxf(fmaxf(t3, t4), x[15]));
               }
               __builtin_amdgcn_sched_barrier(0);
-              if (RED == 1) {        // one value per 32-row block: blocks of a head are merged at the flush
+              if (RED == 1 && !paired) {   // one value per 32-row block: blocks of a head are merged at the flush
                 colsum = max_other_half(colsum);
                 if (half == 0) csum[(size_t)buf * NW * MB * KT + (rb * NW + wv) * KT + kb * 32 + l32] = colsum;
               }
             }
             if (RED == 0) {
               colsum = add_other_half(colsum);
+              if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
+            } else if (paired) {       // the maximum over both blocks of the pair, slot wv
+              colsum = max_other_half(colsum);
               if (half == 0) csum[(size_t)buf * NW * MB * KT + wv * KT + kb * 32 + l32] = colsum;
             }
           }
