@@ -423,6 +423,7 @@ def test_specpc_select_tokens(S, n_in, top_k, nb):
     (2500, 10, 8, 1, 64, 64, 400),      # the hyper-parameter table's SpecPC column: even kernels of 64
     (1200, 3, 1, 1, 32, 32, 150),       # ... and of 32 (the smaller draft)
     (700, 2, 0, 2, 2, 4, 90),           # the smallest even kernels
+    (1800, 3, 1, 64, 7, 9, 200),        # 128 rows per head: full row super-blocks, head maxima merged in pairs
 ])
 def test_specpc_compress_prompt_alg2(S, n_in, n_layers, l_skip, n_lookahead, pool_k, n_neighbor, c_max):
     base = workloads.specpc_draft(n_in=n_in, n_layers=n_layers, name="c5_alg2")
