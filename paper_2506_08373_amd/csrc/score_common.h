@@ -31,6 +31,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
 
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
+// Row statistics against a fixed reference (score_sweep.h): after every kAnchorTiles tiles a row
+// sum that has reached 2^126 (or is not a number) sends the workgroup over those tiles again with
+// the online step.
+constexpr int kAnchorTiles = 16;
+constexpr float kAnchorLimit = 8.507059e37f;
 
 
 // x + (x of the lane 32 away), in every lane, without going through LDS (v_permlane32_swap).

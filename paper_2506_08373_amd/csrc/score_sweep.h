@@ -271,9 +271,22 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
+  // Row statistics of an unmasked chunk.  The chunk's first 32-key block gives each row its reference
+  // exponent (the block's maximum, found by the online step); every later block only adds
+  // 2^(score - reference) to the row's sum: no maximum search, no rescaling.  After every tile the
+  // sum's own exponent moves into the reference (a few integer and float operations, no branch),
+  // which keeps the sum near 2^-shift with shift = 100 - ceil(log2(keys per chunk)): a term that
+  // underflows (below 2^-126) beside it is less than 2^-25 / (keys per chunk) of the sum, so all
+  // of a chunk's keys together stay below fp32 resolution, and a score may exceed everything the
+  // row has seen before its tile by 126 + shift binary orders (146 nats for 32K-key chunks)
+  // before the sum overflows.  An overflow is sticky (infinity stays infinity), so it is looked for
+  // only after every kAnchorTiles tiles (kAnchorLimit; also NaN): the workgroup then restores the
+  // pairs it had before those tiles and sweeps them again with the online step on every block.
+  const int anchor_shift = 100 - (32 - __builtin_clz((unsigned)max(A.g.KC, 2) - 1u));
+
   // one tile of the sweep; the LDS buffer index is a compile-time constant so that every LDS
   // address below is a register plus an immediate
-  auto do_tile = [&](int tile, auto buf_c) {
+  auto do_tile = [&](int tile, auto buf_c, auto anchored_c) {
     constexpr int buf = decltype(buf_c)::value;
     if (tile + 1 < ntiles) SPECKV_LOAD_TILE(tile + 1, buf ^ 1)
     if (PASS == 2 && tile > 0) SPECKV_FLUSH_TILE(tile - 1)
@@ -284,8 +297,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
       // the vector pipe turns the scores into probabilities.  The second wave on the SIMD
       // runs its MFMAs underneath that vector work.
       // NACT = number of active row blocks of this wave (compile-time copy of nact)
-      auto fast_tile = [&](auto nact_c) {
+      // anchored: row statistics against the fixed reference (see above), else the online step
+      auto fast_tile = [&](auto nact_c, auto anchored_c) {
         constexpr int NACT = decltype(nact_c)::value;
+        constexpr bool anchored = decltype(anchored_c)::value;
         u32x4 bf[NCS];
         SPECKV_LOAD_BFRAG(bf, buf, 0)
 #pragma unroll
@@ -306,7 +321,16 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
           if (PASS == 2) __builtin_amdgcn_sched_barrier(0);
           if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
           if (PASS == 2) __builtin_amdgcn_sched_barrier(0);
-          if (PASS == 1) {
+          if (PASS == 1 && anchored && !(kb == 0 && tile == 0)) {
+#pragma unroll
+            for (int rb = 0; rb < NACT; ++rb) {
+              const float nm = -mrun[rb];
+              float sum = 0.f;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nm));
+              lrun[rb] += sum;
+            }
+          } else if (PASS == 1) {
 #pragma unroll
             for (int rb = 0; rb < NACT; ++rb) {
               // branch-free online softmax step for the lane's query row
@@ -322,6 +346,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
               for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[rb][i], c2, nm));
               lrun[rb] = fmaf(lrun[rb], scale, sum);
               mrun[rb] = mnew;
+              if (anchored) {      // the chunk's first block: move the reference up for the blocks that follow
+                lrun[rb] = __builtin_ldexpf(lrun[rb], -anchor_shift);
+                mrun[rb] += (float)anchor_shift;
+              }
             }
           } else {
             // the 16 probabilities of a row block: all multiply-adds, then all exp2, then the reduction
@@ -361,9 +389,17 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
             }
           }
         }
+        if (PASS == 1 && anchored) {   // the sum's exponent above 2^-shift goes into the reference
+#pragma unroll
+          for (int rb = 0; rb < NACT; ++rb) {
+            const int up = max(__builtin_amdgcn_frexp_expf(lrun[rb]) + anchor_shift, 0);
+            lrun[rb] = __builtin_ldexpf(lrun[rb], -up);
+            mrun[rb] += (float)up;
+          }
+        }
       };
-      if (nact == MB) fast_tile(std::integral_constant<int, MB>{});
-      else if (MB > 1 && nact == 1) fast_tile(std::integral_constant<int, 1>{});
+      if (nact == MB) fast_tile(std::integral_constant<int, MB>{}, anchored_c);
+      else if (MB > 1 && nact == 1) fast_tile(std::integral_constant<int, 1>{}, anchored_c);
     } else {
       // Tail tiles: keys above m are hidden from some window rows; keys >= n_s do not exist.
 #pragma unroll 1
@@ -434,9 +470,34 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   };
-  for (int tile = 0; tile < ntiles; tile += 2) {
-    do_tile(tile, std::integral_constant<int, 0>{});
-    if (tile + 1 < ntiles) do_tile(tile + 1, std::integral_constant<int, 1>{});
+  // tiles [t0, t1), t0 even (its tile sits in LDS buffer 0)
+  auto run_tiles = [&](int t0, int t1, auto anchored_c) {
+    for (int tile = t0; tile < t1; tile += 2) {
+      do_tile(tile, std::integral_constant<int, 0>{}, anchored_c);
+      if (tile + 1 < t1) do_tile(tile + 1, std::integral_constant<int, 1>{}, anchored_c);
+    }
+  };
+  if constexpr (PASS == 1 && !MASKED) {
+    for (int t0 = 0; t0 < ntiles; t0 += kAnchorTiles) {
+      const int t1 = min(ntiles, t0 + kAnchorTiles);
+      float m_before[MB], l_before[MB];
+#pragma unroll
+      for (int rb = 0; rb < MB; ++rb) { m_before[rb] = mrun[rb]; l_before[rb] = lrun[rb]; }
+      run_tiles(t0, t1, std::true_type{});
+      bool out_of_range = false;
+#pragma unroll
+      for (int rb = 0; rb < MB; ++rb) out_of_range |= !(lrun[rb] < kAnchorLimit);
+      if (__syncthreads_or(out_of_range)) {            // rare: these tiles again, online step throughout
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb) { mrun[rb] = m_before[rb]; lrun[rb] = l_before[rb]; }
+        SPECKV_LOAD_TILE(t0, 0)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        run_tiles(t0, t1, std::false_type{});
+      }
+    }
+  } else {
+    run_tiles(0, ntiles, std::false_type{});
   }
 
   if (PASS == 1) {
@@ -444,9 +505,15 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
     float2 *pp = A.part + ((int64_t)unit * A.g.n_chunks + chunk) * RSB;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
-      const float mo = __shfl_xor(mrun[rb], 32, 64), lo = __shfl_xor(lrun[rb], 32, 64);
-      const float mm = fmaxf(mrun[rb], mo);
-      const float ll = lrun[rb] * __builtin_amdgcn_exp2f(mrun[rb] - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
+      // A sum taken against a fixed reference can be many binary orders away from 1.  Its exponent
+      // moves into the reference first, so that every pair handed on has a sum in [0.5, 1) (or 0)
+      // and merging two pairs never multiplies a large sum by a factor that underflows.
+      int e2;
+      const float lf = __builtin_frexpf(lrun[rb], &e2);
+      const float mf = mrun[rb] + (float)e2;
+      const float mo = __shfl_xor(mf, 32, 64), lo = __shfl_xor(lf, 32, 64);
+      const float mm = fmaxf(mf, mo);
+      const float ll = lf * __builtin_amdgcn_exp2f(mf - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
       if (half == 0) pp[(rb * NW + wv) * 32 + l32] = make_float2(mm, ll);
     }
   } else if (ntiles > 0) {

@@ -1200,7 +1200,9 @@ def test_half_precision_inputs(S, head_dim, group):
 
 def test_sharp_softmax_large_logits(S):
     """Logits with a standard deviation of tens of nats (max far above 100): rows are nearly one-hot,
-    most probabilities underflow; no overflow, no NaN, and the scores still match the oracle."""
+    most probabilities underflow; no overflow, no NaN, and the scores still match the oracle.
+    The planted keys lie hundreds of nats above everything before them, so the row-statistics sweep
+    overflows its fixed-reference sums there and has to take those tiles again with the online step."""
     w = workloads.SpecKVWorkload(
         name="sharp", n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_lens=(3000, 1500),
         n_window=32, n_lookahead=32, pool_k=7, c_max=300, dtype="bf16", sm_scale=1.0 / math.sqrt(128.0),
@@ -1209,6 +1211,14 @@ def test_sharp_softmax_large_logits(S):
     logits = (t["q"][0, 0, :, 0].float() @ t["k"][0, :3000, 0].float().T) * w.sm_scale
     assert float(logits.std()) > 20 and float(logits.max()) > 100        # the case is what it claims to be
     check_full_path(S, w)
+    # the 8-wave, two-block geometry with chunks longer than 16 tiles, so that the overflow check
+    # and the second sweep over those tiles also run in the middle of a chunk
+    import dataclasses
+    long_w = dataclasses.replace(w, name="sharp_long", n_layers=4, n_q_heads=32, n_kv_heads=8, seq_lens=(17000,),
+                                 n_lookahead=96, n_planted=6, seed=64)
+    info = S.plan_info(make_params(S, long_w))
+    assert info["chunk_keys"] > 16 * info["tile_keys"] and info["blocks_per_wave"] == 2
+    check_full_path(S, long_w)
 
 
 def test_q_stationary_kernel_against_oracle_and_tile_kernel(S, monkeypatch):
