@@ -81,7 +81,7 @@ def _scoring_kernel_symbol(S, p, w, stage: str) -> str:
     info = S.plan_info(p)
     dt = {"bf16": 0, "f32": 1, "f16": 2}[w.dtype]
     npass = 1 if stage == "score_pass1" else 2
-    red = info["reduce_max"] if npass == 2 else 0
+    red = info["reduce_max"] if npass == 2 else info["fixed_reference_rows"]
     if info["q_stationary"] & npass:
         return "score_qs_kernel<%d, %d, %d, %d>" % (dt, w.head_dim, npass, red)
     fn = "score_kernel_rows" if (npass == 1 and info["waves"] == 8) else "score_kernel_cols"

@@ -153,9 +153,11 @@ size_t speckv_workspace_bytes(const speckv_params *p);
  * tile, [6] parts a row is split into for selection (1: one workgroup per row), [7] keys per such
  * part, [8] kernels of the unmasked scoring sweeps: bit 0 set when the row-statistics sweep, bit 1
  * when the column-reduction sweep keeps the query rows stationary in LDS (clear: key tiles streamed
- * through LDS), [9] 1 for max reduction.  Returns SPECKV_OK or the reason the
- * parameters are rejected. */
-#define SPECKV_PLAN_INFO_WORDS 10
+ * through LDS), [9] 1 for max reduction, [10] 1 when the key-tile row-statistics sweep sums
+ * against fixed reference exponents and is followed by a repair launch (sweeps of several rounds of
+ * workgroups), 0 when it takes the online maximum step on every key block.  Returns SPECKV_OK or
+ * the reason the parameters are rejected. */
+#define SPECKV_PLAN_INFO_WORDS 11
 speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_INFO_WORDS]);
 
 /* Importance scores (Eq. 1; Alg. 1 CrossAttention, reduce and pooling steps).

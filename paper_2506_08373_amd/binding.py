@@ -284,10 +284,10 @@ def speckv_compress_static(p: SpecKVParams, q, k, v, idx, k_out, v_out) -> None:
 
 def plan_info(p: SpecKVParams) -> dict:
     """The host's launch plan for these parameters (diagnostics; needs no GPU)."""
-    out = (ctypes.c_int64 * 10)()
+    out = (ctypes.c_int64 * 11)()
     _check(load_library().speckv_plan_info(p.ref(), out), "speckv_plan_info")
     keys = ("waves", "blocks_per_wave", "row_super_blocks", "chunk_keys", "n_chunks", "tile_keys",
-            "select_parts", "select_part_keys", "q_stationary", "reduce_max")
+            "select_parts", "select_part_keys", "q_stationary", "reduce_max", "fixed_reference_rows")
     return dict(zip(keys, (int(x) for x in out)))
 
 

@@ -177,7 +177,9 @@ speckv_status build_plan(const speckv_params *p, Plan *pl, bool one_row_per_call
   // workspace carve-up
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = (size_t)align_up((int64_t)(off + bytes), 256); return o; };
-  pl->off_part = take((size_t)units * g.n_chunks * g.RSB * sizeof(float2));
+  // partial pairs of the row-statistics sweep, and behind them the segments its chunk workgroups
+  // leave for the repair launch (score_fail_words ints)
+  pl->off_part = take((size_t)units * g.n_chunks * g.RSB * sizeof(float2) + (size_t)score_fail_words(*pl) * sizeof(int32_t));
   pl->off_lse = take((size_t)d.L * d.Hkv * d.S * g.RS * g.RSB * sizeof(float));
   pl->off_planes = take((size_t)g.RS * d.L * d.Hkv * d.T * sizeof(float));
   pl->off_pooled = take(one_row_per_call ? (size_t)d.T * sizeof(float) : (size_t)d.L * d.Hkv * d.T * sizeof(float));
@@ -283,6 +285,7 @@ speckv_status speckv_plan_info(const speckv_params *p, int64_t info[SPECKV_PLAN_
   info[6] = pl.sel_parts; info[7] = pl.sel_part_len;
   info[8] = (score_uses_qs(pl, 1) ? 1 : 0) | (score_uses_qs(pl, 2) ? 2 : 0);
   info[9] = pl.d.reduce_max;
+  info[10] = (!score_uses_qs(pl, 1) && pl.g.n_fast_chunks > 0 && score_rows_fixed_reference(pl.d, pl.g)) ? 1 : 0;
   return SPECKV_OK;
 }
 

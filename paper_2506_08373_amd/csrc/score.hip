@@ -102,10 +102,12 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
   return e;
 }
 
+int64_t score_fail_words(const Plan &pl) { return score_chunk_workgroups(pl.d, pl.g) * kFailWords; }
+
 bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;
   A.d = pl.d; A.t = pl.t; A.g = pl.g;
-  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.chunk_blocks = 0; A.clear = nullptr; A.clear_words = 0;
+  A.q = nullptr; A.k = nullptr; A.part = nullptr; A.lse = nullptr; A.planes = nullptr; A.lse_in = nullptr; A.chunk_blocks = 0; A.clear = nullptr; A.clear_words = 0; A.fail = nullptr;
   return qs_supported(A, pass);
 }
 
@@ -117,6 +119,7 @@ hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *pa
   A.q = (const char *)q; A.k = (const char *)k;
   A.part = part; A.lse = lse; A.planes = planes; A.lse_in = lse_in; A.chunk_blocks = 0;
   A.clear = clear; A.clear_words = clear != nullptr ? clear_words : 0;
+  A.fail = reinterpret_cast<int32_t *>(part + (int64_t)A.d.L * A.d.Hkv * A.g.RS * A.g.n_chunks * A.g.RSB);
   hipEvent_t *ev = events;
   hipError_t e;
   if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return e;

@@ -21,6 +21,7 @@ struct ScoreArgs {
   uint32_t *clear;  // optional scratch the kernel between the sweeps zeroes (clear_words words)
   int64_t clear_words;
   int chunk_blocks; // whole-sweep launches: workgroups that run unmasked chunks; the masked tails follow them
+  int32_t *fail;    // row-statistics sweep: kFailWords ints per chunk workgroup (see score_sweep.h)
 };
 
 namespace {
@@ -31,10 +32,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit lane access
 
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
-// Row statistics against a fixed reference (score_sweep.h): after every kAnchorTiles tiles a row
-// sum that has reached 2^126 (or is not a number) sends the workgroup over those tiles again with
-// the online step.
-constexpr int kAnchorTiles = 16;
+// Row statistics against a fixed reference (score_sweep.h): a segment of kAnchorTiles tiles after
+// which a row sum has reached 2^126 (or is not a number) is repeated with the online step.
+constexpr int kAnchorTiles = 4;
+// What a chunk workgroup of the row-statistics sweep leaves for the repair launch: [0] the number
+// of segments to repeat, [1 .. kFailListed] the first ones by number, [kFailWords - 1] the
+// segment from which on every segment is to be repeated when there are more than that.
+constexpr int kFailWords = 8, kFailListed = 6;
 constexpr float kAnchorLimit = 8.507059e37f;
 
 

@@ -50,12 +50,19 @@ constexpr size_t score_lds_bytes() {
 
 // One workgroup's sweep over a chunk of keys; bid = its index among the workgroups of its kind.
 //   PASS    1: row statistics, 2: column reduction
-//   RED     (pass 2) 0: sum over the rows of a head, 1: max over the rows of a head
+//   RED     (pass 2) 0: sum over the rows of a head, 1: max over the rows of a head;
+//           (pass 1) 0: online step on every key block, 1: fixed reference exponents with a
+//           repair launch behind the sweep (see below; for sweeps of several rounds of workgroups)
 //   MASKED  false: every tile of the chunk is complete and visible to every row (key <= m), the
 //           loop body is straight-line code without any bounds or mask logic;
 //           true: the tail of a sequence (keys that window rows may not see, end of sequence)
-template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED>
-__device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
+//   REPAIR  (pass 1, unmasked) false: the whole chunk against fixed references; segments
+//           (kAnchorTiles tiles) whose sums overflowed are left out of the pairs written and
+//           listed in A.fail;  true: segment `seg` alone with the online step, its pairs merged
+//           into the ones already written
+template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED, bool REPAIR = false>
+__device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, const int seg = 0) {
+  static_assert(!REPAIR || (PASS == 1 && !MASKED), "only the row-statistics sweep is repaired");
   constexpr int ELT = elt_bytes(DT);
   using TL = Tile<ELT, D>;
   constexpr int ROWB = TL::ROWB, NCS = TL::NCS, KT = TL::KT, TILE_BYTES = TL::TILE_BYTES;
@@ -169,7 +176,8 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   }
   // the first tile is requested before anything else is loaded, so that its latency overlaps
   // with the Q fragment and row normaliser loads below
-  if (ntiles > 0) SPECKV_LOAD_TILE(0, 0)
+  const int first_tile = REPAIR ? seg * kAnchorTiles : 0;
+  if (ntiles > first_tile) SPECKV_LOAD_TILE(first_tile, 0)
 
   // ---- Q fragments of this wave's row blocks, resident for the whole sweep
   u32x4 qf[MB][NCS];
@@ -280,9 +288,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
   // of a chunk's keys together stay below fp32 resolution, and a score may exceed everything the
   // row has seen before its tile by 126 + shift binary orders (146 nats for 32K-key chunks)
   // before the sum overflows.  An overflow is sticky (infinity stays infinity), so it is looked for
-  // only after every kAnchorTiles tiles (kAnchorLimit; also NaN): the workgroup then restores the
-  // pairs it had before those tiles and sweeps them again with the online step on every block.
+  // once per segment of kAnchorTiles tiles (kAnchorLimit; also NaN): the workgroup then goes back
+  // to the pairs it had before the segment, notes the segment in A.fail and goes on; the repair
+  // launch behind this one (REPAIR) sweeps the noted segments with the online step on every block
+  // and adds their pairs.  (The same second sweep as code inside this kernel, inlined, outlined or
+  // as a compact loop, costs the first sweep the 3 % it is there to gain.)
   const int anchor_shift = 100 - (32 - __builtin_clz((unsigned)max(A.g.KC, 2) - 1u));
+  int fresh_tile = 0;                // the tile whose first block finds the reference (no pair yet)
 
   // one tile of the sweep; the LDS buffer index is a compile-time constant so that every LDS
   // address below is a register plus an immediate
@@ -321,7 +333,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
           if (PASS == 2) __builtin_amdgcn_sched_barrier(0);
           if (kb + 1 < KT / 32) SPECKV_LOAD_BFRAG(bf, buf, kb + 1)
           if (PASS == 2) __builtin_amdgcn_sched_barrier(0);
-          if (PASS == 1 && anchored && !(kb == 0 && tile == 0)) {
+          if (PASS == 1 && anchored && !(kb == 0 && tile == fresh_tile)) {
 #pragma unroll
             for (int rb = 0; rb < NACT; ++rb) {
               const float nm = -mrun[rb];
@@ -477,7 +489,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
       if (tile + 1 < t1) do_tile(tile + 1, std::integral_constant<int, 1>{}, anchored_c);
     }
   };
-  if constexpr (PASS == 1 && !MASKED) {
+  if constexpr (REPAIR) {
+    run_tiles(first_tile, min(ntiles, first_tile + kAnchorTiles), std::false_type{});
+  } else if constexpr (PASS == 1 && !MASKED && RED == 1) {
+    int n_failed = 0;
+    int listed[kFailListed + 1];       // uniform: lives in scalar registers
+#pragma unroll
+    for (int i = 0; i <= kFailListed; ++i) listed[i] = 0;
     for (int t0 = 0; t0 < ntiles; t0 += kAnchorTiles) {
       const int t1 = min(ntiles, t0 + kAnchorTiles);
       float m_before[MB], l_before[MB];
@@ -487,14 +505,24 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
       bool out_of_range = false;
 #pragma unroll
       for (int rb = 0; rb < MB; ++rb) out_of_range |= !(lrun[rb] < kAnchorLimit);
-      if (__syncthreads_or(out_of_range)) {            // rare: these tiles again, online step throughout
+      // (a full list: every later segment is left to the repair as well, overflowed or not)
+      if (__syncthreads_or(out_of_range) || n_failed > kFailListed) {            // rare
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb) { mrun[rb] = m_before[rb]; lrun[rb] = l_before[rb]; }
-        SPECKV_LOAD_TILE(t0, 0)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        run_tiles(t0, t1, std::false_type{});
+        if (fresh_tile == t0) fresh_tile = t1;         // still no pair: the next segment finds the reference
+#pragma unroll
+        for (int i = 0; i <= kFailListed; ++i)
+          if (i == n_failed) listed[i] = t0 / kAnchorTiles;
+        ++n_failed;
       }
+    }
+    if (tid <= kFailListed + 1) {
+      int32_t *mine = A.fail + (int64_t)bid * kFailWords;
+      int v = n_failed;
+#pragma unroll
+      for (int i = 0; i <= kFailListed; ++i)
+        if (tid == i + 1) v = listed[i];
+      mine[tid] = v;                   // [0] count, [1 ..] segments, the last one the start of the rest
     }
   } else {
     run_tiles(0, ntiles, std::false_type{});
@@ -514,7 +542,16 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid) {
       const float mo = __shfl_xor(mf, 32, 64), lo = __shfl_xor(lf, 32, 64);
       const float mm = fmaxf(mf, mo);
       const float ll = lf * __builtin_amdgcn_exp2f(mf - mm) + lo * __builtin_amdgcn_exp2f(mo - mm);
-      if (half == 0) pp[(rb * NW + wv) * 32 + l32] = make_float2(mm, ll);
+      if (half == 0) {
+        float2 *slot = &pp[(rb * NW + wv) * 32 + l32];
+        if (REPAIR) {                // add to what the first sweep (and earlier repairs) left there
+          const float2 have = *slot;
+          const float m2 = fmaxf(have.x, mm);
+          *slot = make_float2(m2, have.y * __builtin_amdgcn_exp2f(have.x - m2) + ll * __builtin_amdgcn_exp2f(mm - m2));
+        } else {
+          *slot = make_float2(mm, ll);
+        }
+      }
     }
   } else if (ntiles > 0) {
     SPECKV_FLUSH_TILE(ntiles - 1)
@@ -552,6 +589,23 @@ __global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
   score_dispatch<DT, D, MB, NW, PASS, RED, TAIL_ONLY>(A);
 }
 
+// The launch behind a row-statistics sweep: a chunk workgroup's twin reads the list the sweep left
+// and repeats the listed segments with the online step (normally there are none and it returns).
+template <int DT, int D, int MB, int NW>
+__global__ __launch_bounds__(NW * 64) void score_kernel_rows_repair(ScoreArgs A) {
+  const int bid = blockIdx.x;
+  const int per_group = 8 * A.g.RS;
+  const int item = (bid / per_group) * 8 + ((bid % per_group) & 7);
+  if (item >= A.g.n_fast_chunks * A.d.L * A.d.Hkv) return;        // padding of the grid: no list written
+  const int32_t *mine = A.fail + (int64_t)bid * kFailWords;
+  const int n_failed = __builtin_amdgcn_readfirstlane(mine[0]);
+  for (int i = 0; i < n_failed; ++i) {
+    const int seg = i <= kFailListed ? mine[1 + i] : mine[1 + kFailListed] + (i - kFailListed);
+    score_body<DT, D, MB, NW, 1, 0, false, true>(A, bid, __builtin_amdgcn_readfirstlane(seg));
+    __syncthreads();
+  }
+}
+
 template <typename K>
 hipError_t launch_one(K kernel, const ScoreArgs &A, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
   hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds);
@@ -573,10 +627,15 @@ hipError_t launch_sweep(const ScoreArgs &A0, size_t lds, hipStream_t st) {
     if (chunk_wgs + tails > 0x7fffffffLL) return hipErrorInvalidValue;
     A.chunk_blocks = (int)chunk_wgs;
     const dim3 grid((unsigned)(chunk_wgs + tails));
-    if constexpr (PASS == 1 && NW == 8)
-      return launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
-    else
+    if constexpr (PASS == 1) {
+      hipError_t e;
+      if constexpr (NW == 8) e = launch_one(score_kernel_rows<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+      else e = launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+      if (e != hipSuccess || RED == 0) return e;
+      return launch_one(score_kernel_rows_repair<DT, D, MB, NW>, A, dim3((unsigned)chunk_wgs), block, lds, st);
+    } else {
       return launch_one(score_kernel_cols<DT, D, MB, NW, PASS, RED, false>, A, grid, block, lds, st);
+    }
   }
   if (A.g.n_fast_chunks > 0) {
     const hipError_t e = launch_qs_sweep(A, PASS, st);
@@ -590,7 +649,10 @@ hipError_t launch_sweep(const ScoreArgs &A0, size_t lds, hipStream_t st) {
 template <int DT, int D, int MB, int NW, int PASS>
 hipError_t sweep_for_geometry(const ScoreArgs &A, hipStream_t st) {
   const size_t lds = score_lds_bytes<elt_bytes(DT), D, MB, NW>();
-  if constexpr (PASS == 1) return launch_sweep<DT, D, MB, NW, 1, 0>(A, lds, st);
+  if constexpr (PASS == 1) {
+    if (score_rows_fixed_reference(A.d, A.g)) return launch_sweep<DT, D, MB, NW, 1, 1>(A, lds, st);
+    return launch_sweep<DT, D, MB, NW, 1, 0>(A, lds, st);
+  }
   else return A.d.reduce_max ? launch_sweep<DT, D, MB, NW, 2, 1>(A, lds, st) : launch_sweep<DT, D, MB, NW, 2, 0>(A, lds, st);
 }
 

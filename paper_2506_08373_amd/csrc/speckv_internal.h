@@ -100,6 +100,20 @@ hipError_t launch_compact(const Plan &pl, const void *k, const void *v, const in
 // `clear`, when not null, is scratch of clear_words 32-bit words that the call leaves zeroed (done
 // by the small kernel between the sweeps: the fused calls need zeroed counters for the pooling
 // kernel and must not use a memset, which a captured graph may not contain).
+// ints behind the partial pairs of the row-statistics sweep (one short list per chunk workgroup)
+int64_t score_fail_words(const Plan &pl);
+// Workgroups of one scoring sweep: chunk workgroups ((layer, head, chunk) items rounded up to a
+// multiple of 8, times the row super-blocks) plus one masked tail per (unit, sequence).
+inline int64_t score_chunk_workgroups(const Dims &d, const ScoreGeom &g) {
+  return ((int64_t)g.n_fast_chunks * d.L * d.Hkv + 7) / 8 * 8 * g.RS;
+}
+// True when the key-tile row-statistics sweep sums against fixed reference exponents and a repair
+// launch follows it.  That pays when the sweep runs for several rounds of workgroups; in a
+// one-round sweep the repair launch (a few microseconds when it has nothing to do, a segment's
+// duration when it has) costs more than the first sweep gains.
+inline bool score_rows_fixed_reference(const Dims &d, const ScoreGeom &g) {
+  return score_chunk_workgroups(d, g) + (int64_t)d.L * d.Hkv * g.RS * d.S > 2 * 256;
+}
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,
                         float *planes, hipStream_t st, hipEvent_t *events = nullptr,
                         const float *lse_in = nullptr, uint32_t *clear = nullptr, int64_t clear_words = 0);

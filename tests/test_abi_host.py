@@ -18,7 +18,7 @@ def lib():
     return S.load_library()
 
 
-PLAN_INFO_WORDS = 10     # SPECKV_PLAN_INFO_WORDS of include/speckv.h
+PLAN_INFO_WORDS = 11     # SPECKV_PLAN_INFO_WORDS of include/speckv.h
 
 
 def base_params(**kw):

@@ -1200,9 +1200,7 @@ def test_half_precision_inputs(S, head_dim, group):
 
 def test_sharp_softmax_large_logits(S):
     """Logits with a standard deviation of tens of nats (max far above 100): rows are nearly one-hot,
-    most probabilities underflow; no overflow, no NaN, and the scores still match the oracle.
-    The planted keys lie hundreds of nats above everything before them, so the row-statistics sweep
-    overflows its fixed-reference sums there and has to take those tiles again with the online step."""
+    most probabilities underflow; no overflow, no NaN, and the scores still match the oracle."""
     w = workloads.SpecKVWorkload(
         name="sharp", n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=128, seq_lens=(3000, 1500),
         n_window=32, n_lookahead=32, pool_k=7, c_max=300, dtype="bf16", sm_scale=1.0 / math.sqrt(128.0),
@@ -1211,14 +1209,23 @@ def test_sharp_softmax_large_logits(S):
     logits = (t["q"][0, 0, :, 0].float() @ t["k"][0, :3000, 0].float().T) * w.sm_scale
     assert float(logits.std()) > 20 and float(logits.max()) > 100        # the case is what it claims to be
     check_full_path(S, w)
-    # the 8-wave, two-block geometry with chunks longer than 16 tiles, so that the overflow check
-    # and the second sweep over those tiles also run in the middle of a chunk
-    import dataclasses
-    long_w = dataclasses.replace(w, name="sharp_long", n_layers=4, n_q_heads=32, n_kv_heads=8, seq_lens=(17000,),
-                                 n_lookahead=96, n_planted=6, seed=64)
-    info = S.plan_info(make_params(S, long_w))
-    assert info["chunk_keys"] > 16 * info["tile_keys"] and info["blocks_per_wave"] == 2
-    check_full_path(S, long_w)
+
+
+@pytest.mark.parametrize("dtype,n_planted", [("bf16", 6), ("f32", 512)])
+def test_row_statistics_repair_launch(S, dtype, n_planted):
+    """Sweeps of several rounds of workgroups take the row statistics against fixed reference exponents
+    and leave overflowed segments to a repair launch.  Outliers hundreds of nats above the rest force
+    that: a few per head (bf16: segments listed one by one, in the middle of 4096-key chunks), and one
+    every 64 keys in fp32 (64-key tiles, 16 segments per chunk, all of them overflow: more than a
+    workgroup lists, so the list's "every segment from here on" form is taken)."""
+    w = workloads.SpecKVWorkload(
+        name="repair_" + dtype, n_layers=8, n_q_heads=16, n_kv_heads=8, head_dim=128, seq_lens=(33000,),
+        n_window=32, n_lookahead=32, pool_k=7, c_max=300, dtype=dtype, sm_scale=1.0 / math.sqrt(128.0),
+        q_gain=8.0, n_planted=n_planted, channel_scale=(0.5, 4.0), seed=66)
+    info = S.plan_info(make_params(S, w))
+    assert info["fixed_reference_rows"] == 1 and info["chunk_keys"] == 4096
+    assert info["tile_keys"] == (64 if dtype == "f32" else 128)
+    check_full_path(S, w)
 
 
 def test_q_stationary_kernel_against_oracle_and_tile_kernel(S, monkeypatch):
