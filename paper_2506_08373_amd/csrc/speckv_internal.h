@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "speckv.h"
 
 namespace speckv {
@@ -111,7 +114,12 @@ inline int64_t score_chunk_workgroups(const Dims &d, const ScoreGeom &g) {
 // launch follows it.  That pays when the sweep runs for several rounds of workgroups; in a
 // one-round sweep the repair launch (a few microseconds when it has nothing to do, a segment's
 // duration when it has) costs more than the first sweep gains.
+// The environment can override the choice (read on every call so that a test can switch it):
+// SPECKV_ROW_STATISTICS=fixed (always) or online (never).
 inline bool score_rows_fixed_reference(const Dims &d, const ScoreGeom &g) {
+  const char *e = std::getenv("SPECKV_ROW_STATISTICS");
+  if (e != nullptr && std::strcmp(e, "fixed") == 0) return true;
+  if (e != nullptr && std::strcmp(e, "online") == 0) return false;
   return score_chunk_workgroups(d, g) + (int64_t)d.L * d.Hkv * g.RS * d.S > 2 * 256;
 }
 hipError_t launch_score(const Plan &pl, const void *q, const void *k, float2 *part, float *lse,

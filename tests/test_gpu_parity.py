@@ -1228,6 +1228,32 @@ def test_row_statistics_repair_launch(S, dtype, n_planted):
     check_full_path(S, w)
 
 
+def test_row_statistics_modes_on_small_shapes(S, monkeypatch):
+    """SPECKV_ROW_STATISTICS=fixed forces the fixed-reference sweep and its repair launch onto calls
+    that would take the online step (one round of workgroups): ragged tails, partly filled row
+    super-blocks, fp32 and fp16 tiles, chunks of one segment, outliers in a chunk's first tile.
+    Both modes must match the oracle."""
+    import dataclasses
+    shapes = [workloads.llama8b_layer(n_in=4096 + 300, c_max=512, name="modes_8b"),
+              workloads.ragged_batch(n_layers=2, lo=200, hi=2500, n_seqs=4, seed=4, name="modes_ragged"),
+              workloads.tiny_fp32(),
+              workloads.SpecKVWorkload(name="modes_sharp", n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                                       seq_lens=(3000, 1500), n_window=32, n_lookahead=32, pool_k=7, c_max=300,
+                                       dtype="bf16", sm_scale=1.0 / math.sqrt(128.0), q_gain=8.0, n_planted=4,
+                                       channel_scale=(0.5, 4.0), seed=61),
+              workloads.SpecKVWorkload(name="modes_f16", n_layers=2, n_q_heads=6, n_kv_heads=2, head_dim=128,
+                                       seq_lens=(1700,), n_window=16, n_lookahead=24, pool_k=7, c_max=200,
+                                       dtype="f16", sm_scale=1.0 / math.sqrt(128.0), n_planted=4,
+                                       channel_scale=(0.5, 4.0), seed=51)]
+    for mode in ("fixed", "online"):
+        monkeypatch.setenv("SPECKV_ROW_STATISTICS", mode)
+        for w in shapes:
+            info = S.plan_info(make_params(S, w))
+            if info["q_stationary"] & 1 == 0 and info["n_chunks"] > 0:
+                assert info["fixed_reference_rows"] == (1 if mode == "fixed" else 0), w.name
+            check_full_path(S, w)
+
+
 def test_q_stationary_kernel_against_oracle_and_tile_kernel(S, monkeypatch):
     """The alternative scoring dataflow (query rows stationary in LDS, SPECKV_SCORE_KERNEL=qs)
     against the oracle on sum and max reduction, G = 4 and G = 7, d = 128 and d = 64, and
