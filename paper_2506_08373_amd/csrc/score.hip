@@ -102,7 +102,7 @@ hipError_t allow_dynamic_lds(const void *kernel, size_t bytes) {
   return e;
 }
 
-int64_t score_fail_words(const Plan &pl) { return score_chunk_workgroups(pl.d, pl.g) * kFailWords; }
+int64_t score_fail_words(const Plan &pl) { return score_chunk_workgroups(pl.d, pl.g) * kFailWaves * kFailWords; }
 
 bool score_uses_qs(const Plan &pl, int pass) {
   ScoreArgs A;

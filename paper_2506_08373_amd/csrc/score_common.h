@@ -35,10 +35,11 @@ constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
 // Row statistics against a fixed reference (score_sweep.h): a segment of kAnchorTiles tiles after
 // which a row sum has reached 2^126 (or is not a number) is repeated with the online step.
 constexpr int kAnchorTiles = 4;
-// What a chunk workgroup of the row-statistics sweep leaves for the repair launch: [0] the number
-// of segments to repeat, [1 .. kFailListed] the first ones by number, [kFailWords - 1] the
-// segment from which on every segment is to be repeated when there are more than that.
-constexpr int kFailWords = 8, kFailListed = 6;
+// What each wavefront of a chunk workgroup of the row-statistics sweep leaves for the repair
+// launch: [0] the number of segments to repeat, [1 .. kFailListed] the first ones by number,
+// [kFailWords - 1] the segment from which on every segment is to be repeated when there are more
+// than that.  A workgroup has kFailWaves such lists (the most waves a workgroup has).
+constexpr int kFailWords = 8, kFailListed = 6, kFailWaves = 8;
 constexpr float kAnchorLimit = 8.507059e37f;
 
 

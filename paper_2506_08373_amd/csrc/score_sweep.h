@@ -56,12 +56,14 @@ constexpr size_t score_lds_bytes() {
 //   MASKED  false: every tile of the chunk is complete and visible to every row (key <= m), the
 //           loop body is straight-line code without any bounds or mask logic;
 //           true: the tail of a sequence (keys that window rows may not see, end of sequence)
-//   REPAIR  (pass 1, unmasked) false: the whole chunk against fixed references; segments
-//           (kAnchorTiles tiles) whose sums overflowed are left out of the pairs written and
-//           listed in A.fail;  true: segment `seg` alone with the online step, its pairs merged
-//           into the ones already written
+//   REPAIR  (pass 1, unmasked) false: the whole chunk against fixed references; every wavefront
+//           leaves the segments (kAnchorTiles tiles) in which one of its sums overflowed out of
+//           its pairs and lists them in A.fail;  true: segment `seg` alone with the online step,
+//           its pairs merged into the ones already written; wavefronts that do not take part
+//           (the segment is not on their list) only help to load the key tiles
 template <int DT, int D, int MB, int NW, int PASS, int RED, bool MASKED, bool REPAIR = false>
-__device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, const int seg = 0) {
+__device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, const int seg = 0,
+                                           const bool wave_takes_part = true) {
   static_assert(!REPAIR || (PASS == 1 && !MASKED), "only the row-statistics sweep is repaired");
   constexpr int ELT = elt_bytes(DT);
   using TL = Tile<ELT, D>;
@@ -119,7 +121,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
   int nblk;
   if (A.g.PPH == 1) nblk = min(A.g.HPS, d.G - rs * A.g.HPS) * (A.g.Rp / 32);
   else nblk = (min(RSB, d.R - (rs % A.g.PPH) * RSB) + 31) / 32;
-  const int nact = __builtin_amdgcn_readfirstlane(max(0, min(MB, (nblk - wv + NW - 1) / NW)));
+  const int nact = wave_takes_part ? __builtin_amdgcn_readfirstlane(max(0, min(MB, (nblk - wv + NW - 1) / NW))) : 0;
   // Maximum over the query rows, full super-block, an even number of blocks per head: the wave
   // takes two neighbouring blocks (2 wv and 2 wv + 1, the same head) instead, merges their
   // column maxima in registers and hands one value per key to the flush, not two.  A maximum
@@ -288,10 +290,10 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
   // of a chunk's keys together stay below fp32 resolution, and a score may exceed everything the
   // row has seen before its tile by 126 + shift binary orders (146 nats for 32K-key chunks)
   // before the sum overflows.  An overflow is sticky (infinity stays infinity), so it is looked for
-  // once per segment of kAnchorTiles tiles (kAnchorLimit; also NaN): the workgroup then goes back
-  // to the pairs it had before the segment, notes the segment in A.fail and goes on; the repair
-  // launch behind this one (REPAIR) sweeps the noted segments with the online step on every block
-  // and adds their pairs.  (The same second sweep as code inside this kernel, inlined, outlined or
+  // once per segment of kAnchorTiles tiles (kAnchorLimit; also NaN): the wavefront then goes back
+  // to the pairs it had before the segment, notes the segment on its list in A.fail and goes on;
+  // the repair launch behind this one (REPAIR) sweeps the noted segments with the online step on
+  // every block and adds their pairs.  (The same second sweep as code inside this kernel, inlined, outlined or
   // as a compact loop, costs the first sweep the 3 % it is there to gain.)
   const int anchor_shift = 100 - (32 - __builtin_clz((unsigned)max(A.g.KC, 2) - 1u));
   int fresh_tile = 0;                // the tile whose first block finds the reference (no pair yet)
@@ -505,8 +507,9 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
       bool out_of_range = false;
 #pragma unroll
       for (int rb = 0; rb < MB; ++rb) out_of_range |= !(lrun[rb] < kAnchorLimit);
-      // (a full list: every later segment is left to the repair as well, overflowed or not)
-      if (__syncthreads_or(out_of_range) || n_failed > kFailListed) {            // rare
+      // The decision is the wavefront's own (its rows are nobody else's): no barrier, no exchange.
+      // (A full list: every later segment is left to the repair as well, overflowed or not.)
+      if (__builtin_amdgcn_ballot_w64(out_of_range) != 0 || n_failed > kFailListed) {            // rare
 #pragma unroll
         for (int rb = 0; rb < MB; ++rb) { mrun[rb] = m_before[rb]; lrun[rb] = l_before[rb]; }
         if (fresh_tile == t0) fresh_tile = t1;         // still no pair: the next segment finds the reference
@@ -516,13 +519,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
         ++n_failed;
       }
     }
-    if (tid <= kFailListed + 1) {
-      int32_t *mine = A.fail + (int64_t)bid * kFailWords;
+    if (lane <= kFailListed + 1) {
+      int32_t *mine = A.fail + ((int64_t)bid * NW + wv) * kFailWords;
       int v = n_failed;
 #pragma unroll
       for (int i = 0; i <= kFailListed; ++i)
-        if (tid == i + 1) v = listed[i];
-      mine[tid] = v;                   // [0] count, [1 ..] segments, the last one the start of the rest
+        if (lane == i + 1) v = listed[i];
+      mine[lane] = v;                  // [0] count, [1 ..] segments, the last one the start of the rest
     }
   } else {
     run_tiles(0, ntiles, std::false_type{});
@@ -589,19 +592,39 @@ __global__ __launch_bounds__(NW * 64) void score_kernel_cols(ScoreArgs A) {
   score_dispatch<DT, D, MB, NW, PASS, RED, TAIL_ONLY>(A);
 }
 
-// The launch behind a row-statistics sweep: a chunk workgroup's twin reads the list the sweep left
-// and repeats the listed segments with the online step (normally there are none and it returns).
+// The launch behind a row-statistics sweep: a chunk workgroup's twin reads the lists its wavefronts
+// left and repeats the listed segments, in ascending order, with the online step (normally there
+// are none and it returns).  Every thread walks all NW lists, so the order needs no exchange.
 template <int DT, int D, int MB, int NW>
 __global__ __launch_bounds__(NW * 64) void score_kernel_rows_repair(ScoreArgs A) {
   const int bid = blockIdx.x;
   const int per_group = 8 * A.g.RS;
   const int item = (bid / per_group) * 8 + ((bid % per_group) & 7);
-  if (item >= A.g.n_fast_chunks * A.d.L * A.d.Hkv) return;        // padding of the grid: no list written
-  const int32_t *mine = A.fail + (int64_t)bid * kFailWords;
-  const int n_failed = __builtin_amdgcn_readfirstlane(mine[0]);
-  for (int i = 0; i < n_failed; ++i) {
-    const int seg = i <= kFailListed ? mine[1 + i] : mine[1 + kFailListed] + (i - kFailListed);
-    score_body<DT, D, MB, NW, 1, 0, false, true>(A, bid, __builtin_amdgcn_readfirstlane(seg));
+  if (item >= A.g.n_fast_chunks * A.d.L * A.d.Hkv) return;        // padding of the grid: no lists written
+  const int32_t *lists = A.fail + (int64_t)bid * NW * kFailWords;
+  const int wv = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  int count[NW], at[NW];
+  int total = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { count[w] = lists[w * kFailWords]; at[w] = 0; total += count[w]; }
+  if (total == 0) return;
+  auto listed = [&](int w, int i) {
+    return i <= kFailListed ? lists[w * kFailWords + 1 + i] : lists[w * kFailWords + 1 + kFailListed] + (i - kFailListed);
+  };
+  for (;;) {
+    int next = 0x7fffffff;
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+      if (at[w] < count[w]) next = min(next, listed(w, at[w]));
+    if (next == 0x7fffffff) break;
+    bool mine = false;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const bool has = at[w] < count[w] && listed(w, at[w]) == next;
+      if (has) ++at[w];
+      if (w == wv) mine = has;
+    }
+    score_body<DT, D, MB, NW, 1, 0, false, true>(A, bid, next, mine);
     __syncthreads();
   }
 }
