@@ -34,7 +34,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit
 constexpr float kNegBig = -1.0e30f;    // finite stand-in for "no key seen yet"
 // Row statistics against a fixed reference (score_sweep.h): a segment of kAnchorTiles tiles after
 // which a row sum has reached 2^126 (or is not a number) is repeated with the online step.
-constexpr int kAnchorTiles = 4;
+constexpr int kAnchorTiles = 2;
 // What each wavefront of a chunk workgroup of the row-statistics sweep leaves for the repair
 // launch: [0] the number of segments to repeat, [1 .. kFailListed] the first ones by number,
 // [kFailWords - 1] the segment from which on every segment is to be repeated when there are more

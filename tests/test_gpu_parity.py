@@ -1216,8 +1216,8 @@ def test_row_statistics_repair_launch(S, dtype, n_planted):
     """Sweeps of several rounds of workgroups take the row statistics against fixed reference exponents
     and leave overflowed segments to a repair launch.  Outliers hundreds of nats above the rest force
     that: a few per head (bf16: segments listed one by one, in the middle of 4096-key chunks), and one
-    every 64 keys in fp32 (64-key tiles, 16 segments per chunk, all of them overflow: more than a
-    workgroup lists, so the list's "every segment from here on" form is taken)."""
+    every 64 keys in fp32 (64-key tiles: every segment of a chunk overflows, far more than a
+    wavefront lists, so the list's "every segment from here on" form is taken)."""
     w = workloads.SpecKVWorkload(
         name="repair_" + dtype, n_layers=8, n_q_heads=16, n_kv_heads=8, head_dim=128, seq_lens=(33000,),
         n_window=32, n_lookahead=32, pool_k=7, c_max=300, dtype=dtype, sm_scale=1.0 / math.sqrt(128.0),
