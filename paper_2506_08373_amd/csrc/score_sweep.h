@@ -283,7 +283,7 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
 
   // Row statistics of an unmasked chunk.  The chunk's first 32-key block gives each row its reference
   // exponent (the block's maximum, found by the online step); every later block only adds
-  // 2^(score - reference) to the row's sum: no maximum search, no rescaling.  After every tile the
+  // 2^(score - reference) to the row's sum: no maximum search, no rescaling.  After every segment the
   // sum's own exponent moves into the reference (a few integer and float operations, no branch),
   // which keeps the sum near 2^-shift with shift = 100 - ceil(log2(keys per chunk)): a term that
   // underflows (below 2^-126) beside it is less than 2^-25 / (keys per chunk) of the sum, so all
@@ -403,14 +403,6 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
             }
           }
         }
-        if (PASS == 1 && anchored) {   // the sum's exponent above 2^-shift goes into the reference
-#pragma unroll
-          for (int rb = 0; rb < NACT; ++rb) {
-            const int up = max(__builtin_amdgcn_frexp_expf(lrun[rb]) + anchor_shift, 0);
-            lrun[rb] = __builtin_ldexpf(lrun[rb], -up);
-            mrun[rb] += (float)up;
-          }
-        }
       };
       if (nact == MB) fast_tile(std::integral_constant<int, MB>{}, anchored_c);
       else if (MB > 1 && nact == 1) fast_tile(std::integral_constant<int, 1>{}, anchored_c);
@@ -517,6 +509,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
         for (int i = 0; i <= kFailListed; ++i)
           if (i == n_failed) listed[i] = t0 / kAnchorTiles;
         ++n_failed;
+      } else {                                         // the sum's exponent above 2^-shift goes into the reference
+#pragma unroll
+        for (int rb = 0; rb < MB; ++rb) {
+          const int up = lrun[rb] > 0.f ? max(__builtin_amdgcn_frexp_expf(lrun[rb]) + anchor_shift, 0) : 0;
+          lrun[rb] = __builtin_ldexpf(lrun[rb], -up);
+          mrun[rb] += (float)up;
+        }
       }
     }
     if (lane <= kFailListed + 1) {
