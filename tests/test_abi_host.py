@@ -207,6 +207,29 @@ def test_plan_of_the_benchmark_configurations(lib):
         unmasked = (n_in - 64 + 1) // kt * kt                       # keys every observation row may see, whole tiles
         assert kc % kt == 0 and one["n_chunks"] == -(-unmasked // kc)
         assert one["n_chunks"] * 8 + 8 <= 256 < -(-unmasked // (kc - kt)) * 8 + 8      # one tile shorter would not fit
+        assert one["fixed_reference_rows"] == 0          # one round of workgroups: online step, no repair launch
+    # sweeps of several rounds sum their row statistics against fixed references; the Q-stationary
+    # kernel (row statistics at d = 64) has its own step
+    assert c3["fixed_reference_rows"] == 1 and c4["fixed_reference_rows"] == 1
+    assert c5["q_stationary"] & 1 and c5["fixed_reference_rows"] == 0 and tiny["fixed_reference_rows"] == 0
+
+
+def test_row_statistics_mode_follows_the_environment(lib, monkeypatch):
+    import workloads
+    w = workloads.llama8b_layer(n_in=32768, n_layers=1)
+    p = S.SpecKVParams(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+                       seq_lens=list(w.seq_lens), n_window=w.n_window, n_lookahead=w.n_lookahead, pool_k=w.pool_k,
+                       c_max=w.c_max, sm_scale=w.sm_scale, dtype=w.torch_dtype)
+    assert S.plan_info(p)["fixed_reference_rows"] == 0
+    monkeypatch.setenv("SPECKV_ROW_STATISTICS", "fixed")
+    assert S.plan_info(p)["fixed_reference_rows"] == 1
+    monkeypatch.setenv("SPECKV_ROW_STATISTICS", "online")
+    full = workloads.llama8b_full_128k()
+    pf = S.SpecKVParams(n_layers=full.n_layers, n_q_heads=full.n_q_heads, n_kv_heads=full.n_kv_heads,
+                        head_dim=full.head_dim, seq_lens=list(full.seq_lens), n_window=full.n_window,
+                        n_lookahead=full.n_lookahead, pool_k=full.pool_k, c_max=full.c_max, sm_scale=full.sm_scale,
+                        dtype=full.torch_dtype)
+    assert S.plan_info(pf)["fixed_reference_rows"] == 0
 
 
 def test_plan_invariants_over_random_shapes(lib):
