@@ -319,6 +319,9 @@ def main() -> int:
         roofline = {"kernel": dk["kernel"], "stage": dominant, "bound": "mfma", "achieved": dk["achieved"],
                     "peak": peak_mfma, "unit": "TFLOP/s", "frac": dk["frac"]}
     roofline.update(traffic=traffic, traffic_source=traffic_src, avg_launch_ms=dk["ms"])
+    if dominant == "score_pass1" and S.plan_info(p)["fixed_reference_rows"]:
+        roofline["avg_launch_note"] = ("the stage between two HIP events: the sweep and the repair launch behind it "
+                                       "(score_kernel_rows_repair, 1 % of the stage)")
 
     ms_per_step = elapsed / args.steps * 1e3
     value = w.key_units / (elapsed / args.steps)
