@@ -288,13 +288,13 @@ __device__ __forceinline__ void score_body(const ScoreArgs &A, const int bid, co
   // which keeps the sum near 2^-shift with shift = 100 - ceil(log2(keys per chunk)): a term that
   // underflows (below 2^-126) beside it is less than 2^-25 / (keys per chunk) of the sum, so all
   // of a chunk's keys together stay below fp32 resolution, and a score may exceed everything the
-  // row has seen before its tile by 126 + shift binary orders (146 nats for 32K-key chunks)
+  // row has seen before its segment by 126 + shift binary orders (146 nats for 32K-key chunks)
   // before the sum overflows.  An overflow is sticky (infinity stays infinity), so it is looked for
   // once per segment of kAnchorTiles tiles (kAnchorLimit; also NaN): the wavefront then goes back
   // to the pairs it had before the segment, notes the segment on its list in A.fail and goes on;
   // the repair launch behind this one (REPAIR) sweeps the noted segments with the online step on
-  // every block and adds their pairs.  (The same second sweep as code inside this kernel, inlined, outlined or
-  // as a compact loop, costs the first sweep the 3 % it is there to gain.)
+  // every block and adds their pairs.  (The same second sweep as code inside this kernel, inlined,
+  // outlined or as a compact loop, costs the first sweep the 3 % it is there to gain.)
   const int anchor_shift = 100 - (32 - __builtin_clz((unsigned)max(A.g.KC, 2) - 1u));
   int fresh_tile = 0;                // the tile whose first block finds the reference (no pair yet)
 
