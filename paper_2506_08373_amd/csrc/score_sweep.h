@@ -7,9 +7,10 @@
 // row softmax of sm_scale*S.  A column sum needs every row's normaliser first, so S is
 // computed twice and never stored:
 //
-//   pass 1  row statistics: per row the running (max, sum of exp2) over the keys of one chunk;
-//           a small kernel merges the chunks into lse2[row] = log2 sum_j 2^(c*S[row,j]),
-//           c = sm_scale*log2(e).
+//   pass 1  row statistics: per row a pair (reference exponent, sum of 2^(c*S - reference)) over
+//           the keys of one chunk, the reference either the running maximum or fixed per chunk
+//           (see score_body); a small kernel merges the chunks into
+//           lse2[row] = log2 sum_j 2^(c*S[row,j]), c = sm_scale*log2(e).
 //   pass 2  column sums: raw[j] = sum_rows 2^(c*S[row,j] - lse2[row]).
 //
 // Work split: a workgroup owns RSB = NW*MB*32 rows (all of them when M <= RSB) and one chunk of
@@ -580,7 +581,7 @@ __device__ __forceinline__ void score_dispatch(const ScoreArgs &A) {
 }
 
 // The row-statistics sweep is compiled for exactly two waves per SIMD (the register allocator
-// then schedules its online-softmax step more freely); the column sweep does better without.
+// then schedules its softmax arithmetic more freely); the column sweep does better without.
 template <int DT, int D, int MB, int NW, int PASS, int RED, bool TAIL_ONLY>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_kernel_rows(ScoreArgs A) {
   score_dispatch<DT, D, MB, NW, PASS, RED, TAIL_ONLY>(A);
